@@ -1,0 +1,172 @@
+/*
+ * nanocp.h -- C ABI of the MI355X (gfx950) DCP decode-attention hot path.
+ *
+ * One GPU's share of a decode step under request-level dynamic context parallelism
+ * (paper: Data Plane, "Decoupled Data-Path Design", Phases 2 and 4):
+ *   Phase 2  every KV-binding instance computes, for each routed query, a partial attention
+ *            output over its LOCAL paged KV shard plus the log-sum-exp (LSE) of the shard's scores;
+ *   Phase 4  the MoE-binding instance merges the partials of a request into exact attention.
+ * The per-instance inputs are the ones Alg. 2 pools: routed Q, block table, attention lengths
+ * (here: token ranges), the local paged KV; the outputs are Res and LSE.
+ *
+ * All pointers marked DEVICE are HIP device pointers owned by the caller (any allocator);
+ * pointers marked HOST are ordinary host memory.  Device calls are asynchronous on the given
+ * hipStream_t (passed as void*; NULL = the default stream) and never synchronise or allocate;
+ * only nanocp_plan_upload allocates (the plan's device copy, freed by nanocp_plan_destroy).
+ * Every function returns a nanocp_status; nothing throws or aborts.  Contents of device
+ * buffers (block-table entries, page ids) are NOT validated: pages named by the block table
+ * for a shard's token range must exist in the pools.
+ *
+ * Memory layouts.  x = 16 bytes / sizeof(kv element): 4 (f32), 8 (bf16), 16 (fp8).
+ *   q            [num_q_rows, Hq, Dk]              q_dtype (f32 or bf16)
+ *   GQA k_pool   [num_pages, Hkv, Dk/x, ps, x]     a page of one kv head is Dk/x runs of ps 16-byte
+ *                                                  vectors; vector (c, t) holds dims [c*x, c*x+x) of token t
+ *   GQA v_pool   [num_pages, Hkv, ps/x, Dv, x]     vector (u, c) holds dim c of tokens [u*x, u*x+x)
+ *   MLA k_pool   [num_pages, ps, Dk]               one latent row per token; V = its first Dv dims; v_pool NULL
+ *   k_scale, v_scale [num_pages, Hkv] float        fp8 only: value = e4m3(byte) * scale   (OCP E4M3FN)
+ *   block_table  [num_bt_rows, max_blocks_per_row] int32 physical page ids; entries beyond a
+ *                                                  shard's range are never read
+ *   out_o        [num_shards, Hq, Dv] float        partial output, normalised over the shard's own tokens
+ *   out_lse      [num_shards, Hq]     float        natural-log LSE of the shard's scaled scores
+ * An empty shard (kv_begin == kv_end) yields out_o = 0, out_lse = -inf.  Token slots of a page
+ * outside [kv_begin, kv_end) may hold anything (NaN included); they are masked.
+ */
+#ifndef NANOCP_H
+#define NANOCP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  NANOCP_OK = 0,
+  NANOCP_EINVAL = 1,       /* null pointer, negative size, kv_end < kv_begin, bad enum */
+  NANOCP_ESHAPE = 2,       /* Hq not a multiple of Hkv, dims/page size not a multiple of x, MLA with Hkv != 1 */
+  NANOCP_EBOUNDS = 3,      /* shard range beyond max_blocks*ps, q_row/bt_row out of range, workspace too small */
+  NANOCP_EUNSUPPORTED = 4, /* dtype combination or shape no compiled kernel handles */
+  NANOCP_ENOMEM = 5,
+  NANOCP_EHIP = 6,         /* a HIP runtime call or kernel launch failed */
+  NANOCP_ESTATE = 7        /* plan not uploaded, or uploaded on another device */
+} nanocp_status;
+
+typedef enum { NANOCP_F32 = 0, NANOCP_BF16 = 1, NANOCP_FP8_E4M3 = 2 } nanocp_dtype;
+typedef enum { NANOCP_GQA = 0, NANOCP_MLA = 1 } nanocp_kind;
+
+/* Attention problem shape.  Supported element types: (q,kv) = (f32,f32), (bf16,bf16), (bf16,fp8). */
+typedef struct {
+  int32_t kind;          /* nanocp_kind */
+  int32_t q_dtype;       /* nanocp_dtype */
+  int32_t kv_dtype;      /* nanocp_dtype */
+  int32_t num_q_heads;   /* Hq */
+  int32_t num_kv_heads;  /* Hkv (1 for MLA) */
+  int32_t head_dim_qk;   /* Dk */
+  int32_t head_dim_v;    /* Dv (MLA: Dv <= Dk) */
+  int32_t page_size;     /* ps, tokens per page */
+  float softmax_scale;   /* score = softmax_scale * <q, k> */
+} nanocp_attn_desc;
+
+/* One shard entry = one row of the attention batch of this instance: a whole local request, or
+ * the locally held slice of a long request (the paper's per-instance KV partition).
+ * Token positions are relative to page 0 of block-table row bt_row and need not be page aligned. */
+typedef struct {
+  int32_t q_row;     /* row of q holding the routed query */
+  int32_t bt_row;    /* row of block_table */
+  int32_t kv_begin;  /* first token */
+  int32_t kv_end;    /* one past the last token */
+} nanocp_shard;
+
+/* One tile of the work-list: a page-aligned piece of one (shard, kv head), run by one workgroup
+ * (`chunk`).  Exposed read-only for inspection and tests. */
+typedef struct {
+  int32_t shard;
+  int32_t kv_head;
+  int32_t q_row;
+  int32_t bt_row;
+  int32_t tok_begin;
+  int32_t tok_end;
+  int32_t dst;     /* >= 0: partial slot in the workspace, reduced later; -1: the (shard, head) has a single tile
+                      that writes out_o / out_lse directly */
+  int32_t chunk;   /* workgroup that executes the tile */
+} nanocp_tile;
+
+typedef struct nanocp_plan nanocp_plan; /* opaque, library-owned */
+
+/*
+ * nanocp_plan_create -- build the split-KV tile work-list for one batch composition (HOST only).
+ * The one-GPU analogue of the paper's balance objective (Dual-balanced Scheduling, WaterFill:
+ * minimise the peak load): the flattened page list of all (shard, kv head) pairs is cut into
+ * `num_chunks` spans of near-equal cost, so a very long shard is spread over many workgroups
+ * while short requests are packed several to a workgroup.  Cuts fall on page boundaries.
+ *   shards            HOST, [num_shards]
+ *   tile_tokens       0 = automatic (cost spread evenly over the GPU); > 0 caps a chunk at this many tokens
+ *   num_cus           compute units to plan for; 0 = query the current HIP device
+ *   out               receives the plan; release with nanocp_plan_destroy
+ * Errors: EINVAL, ESHAPE, EBOUNDS, EUNSUPPORTED, ENOMEM; EHIP only if num_cus == 0 and no device.
+ */
+nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shard* shards, int32_t num_shards,
+                                 int32_t num_q_rows, int32_t num_bt_rows, int32_t max_blocks_per_row,
+                                 int32_t tile_tokens, int32_t num_cus, nanocp_plan** out);
+
+/* Sizes the caller needs: number of tiles, number of chunks (= workgroups launched) and the
+ * bytes of DEVICE workspace nanocp_decode_attn_partial requires (may be 0). Any out pointer may be NULL. */
+nanocp_status nanocp_plan_query(const nanocp_plan* plan, int32_t* num_tiles, int32_t* num_chunks,
+                                size_t* workspace_bytes);
+
+/* HOST view of the tile list (valid until the plan is destroyed). */
+nanocp_status nanocp_plan_tiles(const nanocp_plan* plan, const nanocp_tile** tiles, int32_t* num_tiles);
+
+/* Name of the kernel variant the plan dispatches to ("gqa_mfma_bf16", "gqa_mfma_fp8", "mla_mfma_bf16", "generic"). */
+const char* nanocp_plan_kernel(const nanocp_plan* plan);
+
+/* Copy the work-list to the current device (allocates; asynchronous on `stream`). Call once per plan. */
+nanocp_status nanocp_plan_upload(nanocp_plan* plan, void* stream);
+
+void nanocp_plan_destroy(nanocp_plan* plan);
+
+/*
+ * nanocp_decode_attn_partial -- Phase 2: partial attention + LSE for every shard entry of the plan.
+ *   q, k_pool, v_pool, k_scale, v_scale, block_table   DEVICE, layouts above (v_pool NULL for MLA,
+ *                                                      scales NULL unless fp8); 16-byte aligned
+ *   out_o, out_lse                                     DEVICE, written for every shard
+ *   workspace                                          DEVICE scratch of at least the queried size
+ *                                                      (16-byte aligned; contents need not be preserved)
+ * Two launches on `stream`: the tile kernel, then the per-(shard, head) reduction of tile partials.
+ * Errors: EINVAL (null), ESTATE (plan not uploaded), EBOUNDS (workspace too small), EHIP.
+ */
+nanocp_status nanocp_decode_attn_partial(const nanocp_plan* plan, const void* q, const void* k_pool,
+                                         const void* v_pool, const float* k_scale, const float* v_scale,
+                                         const int32_t* block_table, float* out_o, float* out_lse,
+                                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same, and additionally records per tile the device wall clock (100 MHz ticks) at its start and end into
+ * tile_clock[num_tiles][2] (DEVICE, uint64) -- used to report how much the slowest tile straggles. */
+nanocp_status nanocp_decode_attn_partial_timed(const nanocp_plan* plan, const void* q, const void* k_pool,
+                                               const void* v_pool, const float* k_scale, const float* v_scale,
+                                               const int32_t* block_table, float* out_o, float* out_lse,
+                                               void* workspace, size_t workspace_bytes, uint64_t* tile_clock,
+                                               void* stream);
+
+/*
+ * nanocp_merge_partials -- Phase 4: LSE-based merge.  For output r and head a, over the partials
+ * i in part_index[part_offsets[r] .. part_offsets[r+1]):
+ *     LSE = log sum_i exp(lse_i),   O = sum_i exp(lse_i - LSE) * o_i.
+ *   o_parts    DEVICE [num_parts, Hq, Dv] float   (local partials from nanocp_decode_attn_partial and/or
+ *   lse_parts  DEVICE [num_parts, Hq]     float    partials received from other instances)
+ *   part_offsets DEVICE [num_out + 1] int32; part_index DEVICE [part_offsets[num_out]] int32, or NULL for identity
+ *   out        DEVICE [num_out, Hq, Dv] of out_dtype (NANOCP_F32 or NANOCP_BF16)
+ *   out_lse    DEVICE [num_out, Hq] float, or NULL
+ * Partials with lse = -inf are ignored; if all are, O = 0 and LSE = -inf.  Only Hq and Dv of desc are used.
+ */
+nanocp_status nanocp_merge_partials(const nanocp_attn_desc* desc, const float* o_parts, const float* lse_parts,
+                                    const int32_t* part_offsets, const int32_t* part_index, int32_t num_out,
+                                    void* out, int32_t out_dtype, float* out_lse, void* stream);
+
+const char* nanocp_status_str(nanocp_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NANOCP_H */

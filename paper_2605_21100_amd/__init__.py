@@ -1,0 +1,227 @@
+"""Thin ctypes binding of libnanocp.so (the C ABI in include/nanocp.h).
+
+Argument marshalling only: every step of the decode path runs in the HIP kernels of the
+library.  torch tensors are used as device memory; their data pointers are handed to the
+C functions together with the current torch stream.  If the library has not been built
+the import fails loudly -- there is no fallback path.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnanocp.so")
+
+OK, EINVAL, ESHAPE, EBOUNDS, EUNSUPPORTED, ENOMEM, EHIP, ESTATE = range(8)
+F32, BF16, FP8_E4M3 = 0, 1, 2
+GQA, MLA = 0, 1
+_DTYPES = {"f32": F32, "bf16": BF16, "fp8": FP8_E4M3}
+_KINDS = {"gqa": GQA, "mla": MLA}
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("q_dtype", ctypes.c_int32), ("kv_dtype", ctypes.c_int32),
+                ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+                ("head_dim_qk", ctypes.c_int32), ("head_dim_v", ctypes.c_int32),
+                ("page_size", ctypes.c_int32), ("softmax_scale", ctypes.c_float)]
+
+
+class Shard(ctypes.Structure):
+    _fields_ = [("q_row", ctypes.c_int32), ("bt_row", ctypes.c_int32),
+                ("kv_begin", ctypes.c_int32), ("kv_end", ctypes.c_int32)]
+
+
+class Tile(ctypes.Structure):
+    _fields_ = [("shard", ctypes.c_int32), ("kv_head", ctypes.c_int32), ("q_row", ctypes.c_int32),
+                ("bt_row", ctypes.c_int32), ("tok_begin", ctypes.c_int32), ("tok_end", ctypes.c_int32),
+                ("dst", ctypes.c_int32), ("chunk", ctypes.c_int32)]
+
+
+TILE_DTYPE = np.dtype([(n, np.int32) for n, _ in Tile._fields_])
+
+EXPORTS = ["nanocp_plan_create", "nanocp_plan_query", "nanocp_plan_tiles", "nanocp_plan_kernel",
+           "nanocp_plan_upload", "nanocp_plan_destroy", "nanocp_decode_attn_partial",
+           "nanocp_decode_attn_partial_timed", "nanocp_merge_partials", "nanocp_status_str"]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(or python paper_2605_21100_amd/build.py)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    lib.nanocp_plan_create.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(Shard), i32, i32, i32, i32, i32, i32,
+                                       ctypes.POINTER(vp)]
+    lib.nanocp_plan_query.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(sz)]
+    lib.nanocp_plan_tiles.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(i32)]
+    lib.nanocp_plan_kernel.argtypes = [vp]
+    lib.nanocp_plan_kernel.restype = ctypes.c_char_p
+    lib.nanocp_plan_upload.argtypes = [vp, vp]
+    lib.nanocp_plan_destroy.argtypes = [vp]
+    lib.nanocp_plan_destroy.restype = None
+    lib.nanocp_decode_attn_partial.argtypes = [vp] * 9 + [vp, sz, vp]
+    lib.nanocp_decode_attn_partial_timed.argtypes = [vp] * 9 + [vp, sz, vp, vp]
+    lib.nanocp_merge_partials.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, i32, vp, i32, vp, vp]
+    lib.nanocp_status_str.argtypes = [ctypes.c_int]
+    lib.nanocp_status_str.restype = ctypes.c_char_p
+    return lib
+
+
+_lib = _load()
+
+
+class NanocpError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__(f"{where}: {_lib.nanocp_status_str(self.status).decode()} ({self.status})")
+
+
+def _check(status, where):
+    if status != OK:
+        raise NanocpError(status, where)
+
+
+def make_desc(kind, q_dtype, kv_dtype, num_q_heads, num_kv_heads, head_dim_qk, head_dim_v, page_size,
+              softmax_scale):
+    return AttnDesc(_KINDS.get(kind, kind), _DTYPES.get(q_dtype, q_dtype), _DTYPES.get(kv_dtype, kv_dtype),
+                    num_q_heads, num_kv_heads, head_dim_qk, head_dim_v, page_size, softmax_scale)
+
+
+def _ptr(t):
+    """Device (or None) pointer of a torch tensor."""
+    if t is None:
+        return None
+    assert t.is_contiguous()
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is not None:
+        return ctypes.c_void_p(stream)
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Plan:
+    """nanocp_plan: the tile work-list of one batch composition (host object + device copy)."""
+
+    def __init__(self, desc, shards, num_q_rows, num_bt_rows, max_blocks_per_row, tile_tokens=0, num_cus=0):
+        self.desc = desc
+        shards = np.ascontiguousarray(shards, dtype=np.int32).reshape(-1, 4)
+        self.num_shards = shards.shape[0]
+        self._h = ctypes.c_void_p()
+        sp = shards.ctypes.data_as(ctypes.POINTER(Shard)) if self.num_shards else None
+        _check(_lib.nanocp_plan_create(ctypes.byref(desc), sp, self.num_shards, num_q_rows, num_bt_rows,
+                                       max_blocks_per_row, tile_tokens, num_cus, ctypes.byref(self._h)),
+               "nanocp_plan_create")
+        nt, nc, ws = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_size_t()
+        _check(_lib.nanocp_plan_query(self._h, ctypes.byref(nt), ctypes.byref(nc), ctypes.byref(ws)),
+               "nanocp_plan_query")
+        self.num_tiles, self.num_chunks, self.workspace_bytes = nt.value, nc.value, ws.value
+        self.uploaded = False
+
+    @property
+    def kernel(self):
+        return _lib.nanocp_plan_kernel(self._h).decode()
+
+    def tiles(self):
+        """Host copy of the tile list as a numpy structured array."""
+        p, n = ctypes.c_void_p(), ctypes.c_int32()
+        _check(_lib.nanocp_plan_tiles(self._h, ctypes.byref(p), ctypes.byref(n)), "nanocp_plan_tiles")
+        if n.value == 0:
+            return np.zeros(0, TILE_DTYPE)
+        buf = (ctypes.c_char * (n.value * ctypes.sizeof(Tile))).from_address(p.value)
+        return np.frombuffer(buf, dtype=TILE_DTYPE).copy()
+
+    def upload(self, stream=None):
+        _check(_lib.nanocp_plan_upload(self._h, _stream(stream)), "nanocp_plan_upload")
+        self.uploaded = True
+        return self
+
+    def close(self):
+        if self._h:
+            _lib.nanocp_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def nanocp_plan(desc, shards, num_q_rows, num_bt_rows, max_blocks_per_row, tile_tokens=0, num_cus=0):
+    return Plan(desc, shards, num_q_rows, num_bt_rows, max_blocks_per_row, tile_tokens, num_cus)
+
+
+def nanocp_decode_attn_partial(plan, q, k_pool, v_pool, k_scale, v_scale, block_table, out_o, out_lse,
+                               workspace, tile_clock=None, stream=None):
+    """Phase 2 on the given torch device tensors; results land in out_o / out_lse (float32)."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    args = [plan._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(k_scale), _ptr(v_scale), _ptr(block_table),
+            _ptr(out_o), _ptr(out_lse), _ptr(workspace), ws_bytes]
+    if tile_clock is None:
+        _check(_lib.nanocp_decode_attn_partial(*args, _stream(stream)), "nanocp_decode_attn_partial")
+    else:
+        _check(_lib.nanocp_decode_attn_partial_timed(*args, _ptr(tile_clock), _stream(stream)),
+               "nanocp_decode_attn_partial_timed")
+
+
+def nanocp_merge_partials(desc, o_parts, lse_parts, part_offsets, part_index, num_out, out, out_lse=None,
+                          stream=None):
+    """Phase 4 on device tensors; out is float32 or bfloat16 [num_out, Hq, Dv]."""
+    import torch
+    out_dtype = BF16 if out.dtype == torch.bfloat16 else F32
+    if out.dtype not in (torch.bfloat16, torch.float32):
+        raise NanocpError(EUNSUPPORTED, "nanocp_merge_partials")
+    _check(_lib.nanocp_merge_partials(ctypes.byref(desc), _ptr(o_parts), _ptr(lse_parts), _ptr(part_offsets),
+                                      _ptr(part_index), num_out, _ptr(out), out_dtype, _ptr(out_lse),
+                                      _stream(stream)), "nanocp_merge_partials")
+
+
+# --------------------------------------------------------------------------- convenience for tests / bench
+
+def desc_from(d):
+    """AttnDesc from any object with the generator's field names."""
+    return make_desc(d.kind, d.q_dtype, d.kv_dtype, d.num_q_heads, d.num_kv_heads, d.head_dim_qk,
+                     d.head_dim_v, d.page_size, d.softmax_scale)
+
+
+def to_device(arr, kind=None, device="cuda"):
+    """numpy raw buffer -> torch device tensor of the matching element type (bf16 bits, fp8 bytes)."""
+    import torch
+    if arr is None:
+        return None
+    if arr.dtype == np.uint16:
+        return torch.from_numpy(arr.view(np.int16)).to(device).view(torch.bfloat16)
+    if arr.dtype == np.uint8:
+        return torch.from_numpy(arr).to(device)
+    return torch.from_numpy(arr).to(device)
+
+
+class DeviceBatch:
+    """A synthetic batch resident in HBM plus its plan, outputs and workspace."""
+
+    def __init__(self, batch, tile_tokens=0, num_cus=0, device="cuda"):
+        import torch
+        self.batch = batch
+        d = batch.desc
+        self.desc = desc_from(d)
+        self.q = to_device(batch.q, device=device)
+        self.k_pool = to_device(batch.k_pool, device=device)
+        self.v_pool = to_device(batch.v_pool, device=device)
+        self.k_scale = to_device(batch.k_scale, device=device)
+        self.v_scale = to_device(batch.v_scale, device=device)
+        self.block_table = to_device(batch.block_table, device=device)
+        S = batch.shards.shape[0]
+        self.plan = Plan(self.desc, batch.shards, batch.q.shape[0], batch.block_table.shape[0],
+                         batch.block_table.shape[1], tile_tokens, num_cus).upload()
+        self.out_o = torch.empty((S, d.num_q_heads, d.head_dim_v), dtype=torch.float32, device=device)
+        self.out_lse = torch.empty((S, d.num_q_heads), dtype=torch.float32, device=device)
+        self.workspace = torch.empty(max(self.plan.workspace_bytes, 16), dtype=torch.uint8, device=device)
+
+    def partial(self, tile_clock=None):
+        nanocp_decode_attn_partial(self.plan, self.q, self.k_pool, self.v_pool, self.k_scale, self.v_scale,
+                                   self.block_table, self.out_o, self.out_lse, self.workspace, tile_clock)
+        return self.out_o, self.out_lse

@@ -1,0 +1,188 @@
+// Device entry points: nanocp_decode_attn_partial(_timed), nanocp_merge_partials, and the two small
+// LSE-combine kernels (intra-shard tile reduction, cross-shard merge).
+// Paper: Data Plane, Phase 2 (partial attention + LSE) and Phase 4 (LSE-based merging).
+#include <hip/hip_runtime.h>
+
+#include "plan.h"
+
+namespace nanocp {
+
+hipError_t launch_generic(const nanocp_attn_desc& d, const KParams& p, int num_chunks, hipStream_t st);
+hipError_t launch_gqa_mfma(int variant, const KParams& p, int num_chunks, hipStream_t st);
+
+namespace {
+
+__device__ inline uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// LSE-combine of the tile partials of one (shard, kv head): the same operator as the Phase 4 merge,
+// applied inside the instance.  One workgroup per segment; thread <-> (head, dim) pairs.
+__global__ __launch_bounds__(kThreads) void reduce_tiles_kernel(const Seg* segs, const float* ws_o, const float* ws_lse,
+                                                                float* out_o, float* out_lse, int Hq, int G, int Dv) {
+  const Seg sg = segs[blockIdx.x];
+  const int a0 = sg.kv_head * G;
+  float* o = out_o + ((size_t)sg.shard * Hq + a0) * Dv;
+  float* l = out_lse + (size_t)sg.shard * Hq + a0;
+  for (int i = threadIdx.x; i < G * Dv; i += kThreads) {
+    const int g = i / Dv, dv = i - g * Dv;
+    float top = -INFINITY;
+    for (int k = 0; k < sg.n_parts; ++k) top = fmaxf(top, ws_lse[(size_t)(sg.slot_begin + k) * G + g]);
+    float tot = 0.f, acc = 0.f;
+    for (int k = 0; k < sg.n_parts; ++k) {
+      const size_t slot = (size_t)(sg.slot_begin + k);
+      const float w = expf(ws_lse[slot * G + g] - top);
+      tot += w;
+      acc = fmaf(w, ws_o[(slot * G + g) * Dv + dv], acc);
+    }
+    const bool empty = sg.n_parts == 0;
+    o[i] = empty ? 0.f : acc / tot;
+    if (dv == 0) l[g] = empty ? -INFINITY : top + logf(tot);
+  }
+}
+
+// Phase 4: per (output, head) merge of the partials named by the CSR lists.
+template <bool kBf16Out>
+__global__ __launch_bounds__(kThreads) void merge_kernel(const float* o_parts, const float* lse_parts,
+                                                         const int32_t* part_offsets, const int32_t* part_index,
+                                                         void* out, float* out_lse, int Hq, int Dv) {
+  const int r = blockIdx.x;
+  const int b = part_offsets[r], e = part_offsets[r + 1];
+  for (int i = blockIdx.y * kThreads + threadIdx.x; i < Hq * Dv; i += gridDim.y * kThreads) {
+    const int a = i / Dv;
+    float top = -INFINITY;
+    for (int k = b; k < e; ++k) {
+      const size_t pi = part_index ? part_index[k] : k;
+      top = fmaxf(top, lse_parts[pi * Hq + a]);
+    }
+    float tot = 0.f, acc = 0.f;
+    float res = 0.f, lse = -INFINITY;
+    if (top != -INFINITY) {
+      for (int k = b; k < e; ++k) {
+        const size_t pi = part_index ? part_index[k] : k;
+        const float li = lse_parts[pi * Hq + a];
+        if (li == -INFINITY) continue;  // an empty partial's output is ignored whatever it holds
+        const float w = expf(li - top);
+        tot += w;
+        acc = fmaf(w, o_parts[pi * (size_t)Hq * Dv + i], acc);
+      }
+      res = acc / tot;
+      lse = top + logf(tot);
+    }
+    const size_t oi = (size_t)r * Hq * Dv + i;
+    if (kBf16Out)
+      ((uint16_t*)out)[oi] = f32_to_bf16_rne(res);
+    else
+      ((float*)out)[oi] = res;
+    if (out_lse && i - a * Dv == 0) out_lse[(size_t)r * Hq + a] = lse;
+  }
+}
+
+nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_pool, const void* v_pool,
+                          const float* k_scale, const float* v_scale, const int32_t* block_table, float* out_o,
+                          float* out_lse, void* workspace, size_t workspace_bytes, uint64_t* tile_clock, void* stream) {
+  if (!plan) return NANOCP_EINVAL;
+  const nanocp_attn_desc& d = plan->desc;
+  if (plan->num_shards == 0) return NANOCP_OK;
+  if (!q || !k_pool || !block_table || !out_o || !out_lse) return NANOCP_EINVAL;
+  if (d.kind == NANOCP_GQA && !v_pool) return NANOCP_EINVAL;
+  if (d.kv_dtype == NANOCP_FP8_E4M3 && (!k_scale || !v_scale)) return NANOCP_EINVAL;
+  if (plan->device < 0) return NANOCP_ESTATE;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return NANOCP_EHIP;
+  if (dev != plan->device) return NANOCP_ESTATE;
+  if (plan->workspace_bytes > 0 && (!workspace || workspace_bytes < plan->workspace_bytes)) return NANOCP_EBOUNDS;
+  if (((uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)workspace | (uintptr_t)out_o) & 15)
+    return NANOCP_EINVAL;
+
+  hipStream_t st = (hipStream_t)stream;
+  const int G = d.num_q_heads / d.num_kv_heads;
+  KParams p;
+  p.q = q;
+  p.k_pool = k_pool;
+  p.v_pool = v_pool;
+  p.k_scale = k_scale;
+  p.v_scale = v_scale;
+  p.block_table = block_table;
+  p.out_o = out_o;
+  p.out_lse = out_lse;
+  const size_t o_bytes = ((size_t)plan->num_slots * G * d.head_dim_v * sizeof(float) + 255) & ~(size_t)255;
+  p.ws_o = (float*)workspace;
+  p.ws_lse = (float*)((char*)workspace + o_bytes);
+  p.tiles = plan->d_tiles;
+  p.chunk_offsets = plan->d_chunk_offsets;
+  p.tile_clock = tile_clock;
+  p.Hq = d.num_q_heads;
+  p.Hkv = d.num_kv_heads;
+  p.G = G;
+  p.Dk = d.head_dim_qk;
+  p.Dv = d.head_dim_v;
+  p.ps = d.page_size;
+  p.max_blocks = plan->max_blocks;
+  p.kind = d.kind;
+  p.scale = d.softmax_scale;
+
+  if (plan->num_chunks > 0) {
+    hipError_t e;
+    if (plan->variant == kGeneric)
+      e = launch_generic(d, p, plan->num_chunks, st);
+    else
+      e = launch_gqa_mfma(plan->variant, p, plan->num_chunks, st);
+    if (e != hipSuccess) return NANOCP_EHIP;
+  }
+  if (!plan->segs.empty()) {
+    hipLaunchKernelGGL(reduce_tiles_kernel, dim3((unsigned)plan->segs.size()), dim3(kThreads), 0, st, plan->d_segs,
+                       p.ws_o, p.ws_lse, out_o, out_lse, p.Hq, G, p.Dv);
+    if (hipGetLastError() != hipSuccess) return NANOCP_EHIP;
+  }
+  return NANOCP_OK;
+}
+
+}  // namespace
+}  // namespace nanocp
+
+extern "C" {
+
+nanocp_status nanocp_decode_attn_partial(const nanocp_plan* plan, const void* q, const void* k_pool,
+                                         const void* v_pool, const float* k_scale, const float* v_scale,
+                                         const int32_t* block_table, float* out_o, float* out_lse, void* workspace,
+                                         size_t workspace_bytes, void* stream) {
+  return nanocp::run_partial(plan, q, k_pool, v_pool, k_scale, v_scale, block_table, out_o, out_lse, workspace,
+                             workspace_bytes, nullptr, stream);
+}
+
+nanocp_status nanocp_decode_attn_partial_timed(const nanocp_plan* plan, const void* q, const void* k_pool,
+                                               const void* v_pool, const float* k_scale, const float* v_scale,
+                                               const int32_t* block_table, float* out_o, float* out_lse,
+                                               void* workspace, size_t workspace_bytes, uint64_t* tile_clock,
+                                               void* stream) {
+  if (!tile_clock) return NANOCP_EINVAL;
+  return nanocp::run_partial(plan, q, k_pool, v_pool, k_scale, v_scale, block_table, out_o, out_lse, workspace,
+                             workspace_bytes, tile_clock, stream);
+}
+
+nanocp_status nanocp_merge_partials(const nanocp_attn_desc* desc, const float* o_parts, const float* lse_parts,
+                                    const int32_t* part_offsets, const int32_t* part_index, int32_t num_out, void* out,
+                                    int32_t out_dtype, float* out_lse, void* stream) {
+  if (!desc || num_out < 0) return NANOCP_EINVAL;
+  if (desc->num_q_heads <= 0 || desc->head_dim_v <= 0) return NANOCP_EINVAL;
+  if (out_dtype != NANOCP_F32 && out_dtype != NANOCP_BF16) return NANOCP_EUNSUPPORTED;
+  if (num_out == 0) return NANOCP_OK;
+  if (!o_parts || !lse_parts || !part_offsets || !out) return NANOCP_EINVAL;
+  const int Hq = desc->num_q_heads, Dv = desc->head_dim_v;
+  const int per_out = (Hq * Dv + nanocp::kThreads - 1) / nanocp::kThreads;
+  dim3 grid((unsigned)num_out, (unsigned)(per_out < 8 ? per_out : 8));
+  hipStream_t st = (hipStream_t)stream;
+  if (out_dtype == NANOCP_BF16)
+    hipLaunchKernelGGL((nanocp::merge_kernel<true>), grid, dim3(nanocp::kThreads), 0, st, o_parts, lse_parts,
+                       part_offsets, part_index, out, out_lse, Hq, Dv);
+  else
+    hipLaunchKernelGGL((nanocp::merge_kernel<false>), grid, dim3(nanocp::kThreads), 0, st, o_parts, lse_parts,
+                       part_offsets, part_index, out, out_lse, Hq, Dv);
+  return hipGetLastError() == hipSuccess ? NANOCP_OK : NANOCP_EHIP;
+}
+
+}  // extern "C"

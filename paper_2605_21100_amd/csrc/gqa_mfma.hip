@@ -1,0 +1,385 @@
+// MFMA tile kernels for GQA decode with 16 query heads per kv head, head dim 128, page size 64:
+// bf16 KV and fp8 (OCP E4M3FN) KV.  Paper: Data Plane, Phase 2 (partial attention + LSE over the
+// local KV partition).
+//
+// Work split.  One workgroup (4 wavefronts) runs the tiles of one chunk of the work-list.  Inside
+// a tile the wavefronts take alternate steps of kStep tokens (32 for bf16, 64 for fp8), each keeping
+// its own running max / sum / accumulator; they are combined through LDS once per tile.
+//
+// Data path.  K and V go from HBM straight into MFMA operand registers: the page layouts
+// ([Dk/x][ps][x] for K, [ps/x][Dv][x] for V, x = elements per 16 bytes) make every 16-byte vector a
+// ready operand fragment, and 16 consecutive lanes read 64..256 contiguous bytes.
+//   scores:  S^T[token, head] = K[token, :] . Q[head, :]        v_mfma_f32_16x16x32_bf16, A = K, B = Q^T
+//   output:  O^T[dim,  head] += V^T[dim, token] P^T[token, head]                       A = V^T, B = P^T
+// The C layout of the first product (lane = head + 16*g holds 4 token rows 4g..4g+3) is turned into
+// the B layout of the second (lane holds 8 consecutive k) by choosing which token each row of the
+// score MFMA stands for; no cross-lane data movement is needed.
+// P is split into two bf16 terms (hi + lo) so that the P*V product keeps ~16 bits of P.
+// fp8 K/V are widened to bf16 in registers (exact); the per-(page, head) scales are applied to the
+// scores (K) and to P (V) in fp32.
+#include <hip/hip_runtime.h>
+
+#include "plan.h"
+
+namespace nanocp {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kG = 16;    // query heads per kv head
+constexpr int kD = 128;   // head dim (qk and v)
+constexpr int kPS = 64;   // page size
+constexpr int kWaves = kThreads / 64;
+constexpr int kOPad = kD + 4;  // LDS row stride (floats) of the combine buffer
+
+__device__ inline f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ inline u32x4 ldg16(const void* base, uint32_t byte_off) {
+  return *(const u32x4*)((const char*)base + byte_off);
+}
+
+__device__ inline uint32_t pack_bf16(float a, float b) {
+  bf16x2 v = {(__bf16)a, (__bf16)b};  // round to nearest even
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// two OCP E4M3 bytes (low or high half of w) -> two bf16, exact
+template <bool kHi>
+__device__ inline uint32_t fp8x2_to_bf16x2(uint32_t w) {
+  f32x2 f = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, kHi);
+  return pack_bf16(f.x, f.y);
+}
+
+// 8 fp8 bytes (two dwords) -> 8 bf16
+__device__ inline bf16x8 widen8(uint32_t w0, uint32_t w1) {
+  u32x4 r = {fp8x2_to_bf16x2<false>(w0), fp8x2_to_bf16x2<true>(w0), fp8x2_to_bf16x2<false>(w1),
+             fp8x2_to_bf16x2<true>(w1)};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+__device__ inline float xor_max(float v) {
+  v = fmaxf(v, __shfl_xor(v, 16));
+  return fmaxf(v, __shfl_xor(v, 32));
+}
+__device__ inline float xor_sum(float v) {
+  v += __shfl_xor(v, 16);
+  return v + __shfl_xor(v, 32);
+}
+
+// hi/lo bf16 split of 8 probabilities -> two B operands
+__device__ inline void split8(const float* p, bf16x8& hi, bf16x8& lo) {
+  u32x4 h, l;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t hp = pack_bf16(p[2 * i], p[2 * i + 1]);
+    const float h0 = __uint_as_float(hp << 16), h1 = __uint_as_float(hp & 0xffff0000u);
+    h[i] = hp;
+    l[i] = pack_bf16(p[2 * i] - h0, p[2 * i + 1] - h1);
+  }
+  hi = __builtin_bit_cast(bf16x8, h);
+  lo = __builtin_bit_cast(bf16x8, l);
+}
+
+template <bool kFp8>
+struct StepRegs {
+  // bf16: 32 tokens -> K 2 blocks x 4 k-steps, V 8 dim blocks, 16 bytes each
+  // fp8:  64 tokens -> K 4 blocks x 2 loads (16 dims each), V 8 dim blocks (16 tokens each)
+  u32x4 k[8];
+  u32x4 v[8];
+  float ks, vs;  // fp8 scales of the step's page
+};
+
+template <bool kFp8>
+__global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
+  constexpr int kStep = kFp8 ? 64 : 32;            // tokens per step
+  constexpr int kEl = kFp8 ? 1 : 2;                // bytes per kv element
+  constexpr int kBlocks = kStep / 16;              // score MFMA blocks per step
+  constexpr uint32_t kPageHeadBytes = kPS * kD * kEl;  // one (page, kv head) of K or of V
+  constexpr int kNS = kStep / 4;                   // scores per lane per step
+
+  __shared__ float o_s[kWaves][kG][kOPad];
+  __shared__ float m_s[kWaves][kG], l_s[kWaves][kG];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, g = lane >> 4;
+  const int Hkv = p.Hkv;
+  const float c_log2 = p.scale * 1.4426950408889634f;
+
+  // per-lane byte offsets inside a (page, head) block; the step's slot offset is added per step
+  // K vector (c, t) at (c*ps + t)*16.   score block b, row r  <->  token  slot0 + tokmap(r) + 4b
+  const int tokmap = kFp8 ? (16 * (r >> 2) + (r & 3)) : (8 * (r >> 2) + (r & 3));
+  const uint32_t k_lane = (uint32_t)((g * kPS + tokmap) * 16);
+  // V vector (u, c) at (u*Dv + c)*16.   lane (r, g): token group slot0/x + g, dim 16j + r
+  const uint32_t v_lane = (uint32_t)((g * kD + r) * 16);
+
+  const int t0 = p.chunk_offsets[blockIdx.x], t1 = p.chunk_offsets[blockIdx.x + 1];
+  for (int ti = t0; ti < t1; ++ti) {
+    const nanocp_tile tile = p.tiles[ti];
+    uint64_t clk0 = 0;
+    if (p.tile_clock && tid == 0) clk0 = wall_clock64();
+    const int h = tile.kv_head;
+    const int32_t* __restrict__ bt = p.block_table + (size_t)tile.bt_row * p.max_blocks;
+    const int tb = tile.tok_begin, te = tile.tok_end;
+
+    // Q fragments (B operand): lane (g, n = r) holds Q[n][dims of k-step s]
+    bf16x8 qf[4];
+    {
+      const char* qrow = (const char*)p.q + ((size_t)tile.q_row * p.Hq + (size_t)h * kG + r) * kD * 2;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        // bf16 KV: k-step s, group g <-> dim chunk 4s+g (8 dims).
+        // fp8 KV:  load u = s/2 brings dims 16(g+4u)..+16; k-step s takes its half s%2.
+        const int dim0 = kFp8 ? (16 * (g + 4 * (s >> 1)) + 8 * (s & 1)) : (8 * (4 * s + g));
+        qf[s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + dim0 * 2));
+      }
+    }
+
+    f32x4 acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY;  // running max of scaled (log2-domain) scores of head r
+    float l_run = 0.f;        // this lane's share of the running sum
+
+    const int u_end = (te + kStep - 1) / kStep;
+    int u = tb / kStep + wave;
+
+    auto load_step = [&](StepRegs<kFp8>& sr, int uu) {
+      const int tok0 = uu * kStep;
+      const int page = bt[tok0 / kPS];
+      const uint32_t slot0 = (uint32_t)(tok0 % kPS);
+      const size_t ph = ((size_t)page * Hkv + h) * kPageHeadBytes;
+      const char* kb = (const char*)p.k_pool + ph;
+      const char* vb = (const char*)p.v_pool + ph;
+      if (kFp8) {
+        sr.ks = p.k_scale[(size_t)page * Hkv + h];
+        sr.vs = p.v_scale[(size_t)page * Hkv + h];
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+          for (int q2 = 0; q2 < 2; ++q2)
+            sr.k[b * 2 + q2] = ldg16(kb, k_lane + (uint32_t)((4 * q2 * kPS + slot0 + 4 * b) * 16));
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sr.v[j] = ldg16(vb, v_lane + (uint32_t)(((slot0 / 16) * kD + 16 * j) * 16));
+      } else {
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int s = 0; s < 4; ++s)
+            sr.k[b * 4 + s] = ldg16(kb, k_lane + (uint32_t)((4 * s * kPS + slot0 + 4 * b) * 16));
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sr.v[j] = ldg16(vb, v_lane + (uint32_t)(((slot0 / 8) * kD + 16 * j) * 16));
+      }
+    };
+
+    auto compute_step = [&](StepRegs<kFp8>& sr, int uu) {
+      const int tok0 = uu * kStep;
+      const bool ragged = tok0 < tb || tok0 + kStep > te;  // wavefront-uniform
+      // ---- scores
+      f32x4 S[kBlocks];
+#pragma unroll
+      for (int b = 0; b < kBlocks; ++b) {
+        S[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (kFp8) {
+#pragma unroll
+          for (int q2 = 0; q2 < 2; ++q2) {
+            const u32x4 w = sr.k[b * 2 + q2];
+            S[b] = mfma16(widen8(w[0], w[1]), qf[2 * q2], S[b]);
+            S[b] = mfma16(widen8(w[2], w[3]), qf[2 * q2 + 1], S[b]);
+          }
+        } else {
+#pragma unroll
+          for (int s = 0; s < 4; ++s) S[b] = mfma16(__builtin_bit_cast(bf16x8, sr.k[b * 4 + s]), qf[s], S[b]);
+        }
+      }
+      // ---- online softmax in the log2 domain.  S[b][i] is token tok0 + x*g + 4b + i (x = tokens per V vector)
+      const float cs = kFp8 ? c_log2 * sr.ks : c_log2;
+      float y[kNS];
+      float mloc = -INFINITY;
+#pragma unroll
+      for (int b = 0; b < kBlocks; ++b)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float v = S[b][i] * cs;
+          if (ragged) {
+            const int tok = tok0 + (kFp8 ? 16 : 8) * g + 4 * b + i;
+            v = (tok >= tb && tok < te) ? v : -INFINITY;
+          }
+          y[b * 4 + i] = v;
+          mloc = fmaxf(mloc, v);
+        }
+      mloc = xor_max(mloc);
+      const float m_new = fmaxf(m_run, mloc);  // finite: every step overlaps the tile's range
+      if (__any(m_new > m_run)) {
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= alpha;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] *= alpha;
+        m_run = m_new;
+      }
+      float pr[kNS];
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < kNS; ++e) {
+        pr[e] = __builtin_amdgcn_exp2f(y[e] - m_run);
+        psum += pr[e];
+      }
+      l_run += psum;
+      if (kFp8) {
+#pragma unroll
+        for (int e = 0; e < kNS; ++e) pr[e] *= sr.vs;
+      }
+      // ---- mask unused token slots of V (they may hold NaN patterns)
+      if (ragged) {
+        if (kFp8) {
+          // lane's V vector j: bytes e = 0..15 <-> tokens tok0 + 16g + e
+          u32x4 mk;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            uint32_t mw = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int tok = tok0 + 16 * g + 4 * w + e;
+              if (tok >= tb && tok < te) mw |= 0xffu << (8 * e);
+            }
+            mk[w] = mw;
+          }
+#pragma unroll
+          for (int j = 0; j < 8; ++j) sr.v[j] &= mk;
+        } else {
+          u32x4 mk;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            uint32_t mw = 0;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+              const int tok = tok0 + 8 * g + 2 * w + e;
+              if (tok >= tb && tok < te) mw |= 0xffffu << (16 * e);
+            }
+            mk[w] = mw;
+          }
+#pragma unroll
+          for (int j = 0; j < 8; ++j) sr.v[j] &= mk;
+        }
+      }
+      // ---- O^T += V^T P^T
+      if (kFp8) {
+        bf16x8 hi0, lo0, hi1, lo1;  // tokens 16g+0..7 (score blocks 0,1) and 16g+8..15 (blocks 2,3)
+        split8(pr, hi0, lo0);
+        split8(pr + 8, hi1, lo1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const u32x4 w = sr.v[j];
+          const bf16x8 va = widen8(w[0], w[1]), vb2 = widen8(w[2], w[3]);
+          acc[j] = mfma16(va, hi0, acc[j]);
+          acc[j] = mfma16(va, lo0, acc[j]);
+          acc[j] = mfma16(vb2, hi1, acc[j]);
+          acc[j] = mfma16(vb2, lo1, acc[j]);
+        }
+      } else {
+        bf16x8 hi, lo;
+        split8(pr, hi, lo);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const bf16x8 va = __builtin_bit_cast(bf16x8, sr.v[j]);
+          acc[j] = mfma16(va, hi, acc[j]);
+          acc[j] = mfma16(va, lo, acc[j]);
+        }
+      }
+    };
+
+    StepRegs<kFp8> ra, rb;
+    if (u < u_end) load_step(ra, u);
+    while (u < u_end) {
+      int un = u + kWaves;
+      if (un < u_end) load_step(rb, un);
+      compute_step(ra, u);
+      u = un;
+      if (u >= u_end) break;
+      un = u + kWaves;
+      if (un < u_end) load_step(ra, un);
+      compute_step(rb, u);
+      u = un;
+    }
+
+    // ---- combine the 4 wavefronts' partials
+    l_run = xor_sum(l_run);
+    if (g == 0) {
+      m_s[wave][r] = m_run;
+      l_s[wave][r] = l_run;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) *(f32x4*)&o_s[wave][r][16 * j + 4 * g] = acc[j];  // rows 4g+i of block j = dims 16j+4g+i
+    __syncthreads();
+    {
+      // thread <-> (head n, 8 consecutive dims)
+      const int n = tid >> 4, d0 = (tid & 15) * 8;
+      float mw[kWaves], M = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        mw[w] = m_s[w][n];
+        M = fmaxf(M, mw[w]);
+      }
+      float L = 0.f, f[kWaves];
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        f[w] = __builtin_amdgcn_exp2f(mw[w] - M);  // a wavefront without steps has m = -inf -> weight 0
+        L += f[w] * l_s[w][n];
+      }
+      const float inv = 1.f / L;
+      float o[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const f32x4 a = *(const f32x4*)&o_s[w][n][d0], b = *(const f32x4*)&o_s[w][n][d0 + 4];
+        const float fw = f[w] * inv;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          o[e] = fmaf(fw, a[e], o[e]);
+          o[4 + e] = fmaf(fw, b[e], o[4 + e]);
+        }
+      }
+      float* dst_o;
+      float* dst_l;
+      if (tile.dst >= 0) {
+        dst_o = p.ws_o + (size_t)tile.dst * kG * kD;
+        dst_l = p.ws_lse + (size_t)tile.dst * kG;
+      } else {
+        dst_o = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG) * kD;
+        dst_l = p.out_lse + (size_t)tile.shard * p.Hq + (size_t)h * kG;
+      }
+      *(f32x4*)(dst_o + n * kD + d0) = f32x4{o[0], o[1], o[2], o[3]};
+      *(f32x4*)(dst_o + n * kD + d0 + 4) = f32x4{o[4], o[5], o[6], o[7]};
+      if ((tid & 15) == 0) dst_l[n] = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
+    }
+    __syncthreads();
+    if (p.tile_clock && tid == 0) {
+      p.tile_clock[2 * (size_t)ti] = clk0;
+      p.tile_clock[2 * (size_t)ti + 1] = wall_clock64();
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_gqa_mfma(int variant, const KParams& p, int num_chunks, hipStream_t st) {
+  dim3 grid(num_chunks), block(kThreads);
+  if (variant == kGqaMfmaBf16)
+    hipLaunchKernelGGL((gqa_mfma_kernel<false>), grid, block, 0, st, p);
+  else if (variant == kGqaMfmaFp8)
+    hipLaunchKernelGGL((gqa_mfma_kernel<true>), grid, block, 0, st, p);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+}  // namespace nanocp

@@ -1,0 +1,261 @@
+// Host planner: builds the split-KV tile work-list (nanocp_plan_create and friends).
+//
+// The flattened list of pages of all (shard, kv head) pairs is cut into spans of near-equal
+// cost, one span ("chunk") per workgroup.  A span that ends inside a (shard, head) leaves that
+// pair with several tiles whose partials are reduced afterwards; pairs that fall entirely
+// inside one span write their result directly.  This is the one-GPU analogue of the paper's
+// balance objective (Dual-balanced Scheduling / WaterFill: minimise the peak load).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <new>
+
+#include "plan.h"
+
+using namespace nanocp;
+
+namespace {
+
+int elem_bytes(int dt) { return dt == NANOCP_F32 ? 4 : dt == NANOCP_BF16 ? 2 : 1; }
+
+nanocp_status check_desc(const nanocp_attn_desc& d) {
+  if (d.kind != NANOCP_GQA && d.kind != NANOCP_MLA) return NANOCP_EINVAL;
+  if (d.q_dtype < 0 || d.q_dtype > 2 || d.kv_dtype < 0 || d.kv_dtype > 2) return NANOCP_EINVAL;
+  if (d.num_q_heads <= 0 || d.num_kv_heads <= 0 || d.head_dim_qk <= 0 || d.head_dim_v <= 0 || d.page_size <= 0)
+    return NANOCP_EINVAL;
+  if (!(d.softmax_scale == d.softmax_scale)) return NANOCP_EINVAL;
+  if (d.num_q_heads % d.num_kv_heads) return NANOCP_ESHAPE;
+  const int x = 16 / elem_bytes(d.kv_dtype);
+  if (d.kind == NANOCP_MLA) {
+    if (d.num_kv_heads != 1 || d.head_dim_v > d.head_dim_qk) return NANOCP_ESHAPE;
+    if (d.head_dim_qk % x) return NANOCP_ESHAPE;
+  } else {
+    if (d.head_dim_qk % x || d.page_size % x) return NANOCP_ESHAPE;
+  }
+  const bool combo = (d.q_dtype == NANOCP_F32 && d.kv_dtype == NANOCP_F32) ||
+                     (d.q_dtype == NANOCP_BF16 && d.kv_dtype == NANOCP_BF16) ||
+                     (d.q_dtype == NANOCP_BF16 && d.kv_dtype == NANOCP_FP8_E4M3);
+  if (!combo) return NANOCP_EUNSUPPORTED;
+  if (d.kind == NANOCP_MLA && d.kv_dtype == NANOCP_FP8_E4M3) return NANOCP_EUNSUPPORTED;
+  if (d.head_dim_qk > 576 || d.head_dim_v > 512) return NANOCP_EUNSUPPORTED;  // generic kernel's LDS/register budget
+  return NANOCP_OK;
+}
+
+int pick_variant(const nanocp_attn_desc& d) {
+  const int G = d.num_q_heads / d.num_kv_heads;
+  if (d.kind == NANOCP_GQA && d.q_dtype == NANOCP_BF16 && G == 16 && d.head_dim_qk == 128 && d.head_dim_v == 128) {
+    if (d.kv_dtype == NANOCP_BF16 && d.page_size == 64) return kGqaMfmaBf16;
+    if (d.kv_dtype == NANOCP_FP8_E4M3 && d.page_size == 64) return kGqaMfmaFp8;
+  }
+  return kGeneric;
+}
+
+int workgroups_per_cu(int variant) {
+  (void)variant;
+  return 2;
+}
+
+}  // namespace
+
+extern "C" {
+
+nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shard* shards, int32_t num_shards,
+                                 int32_t num_q_rows, int32_t num_bt_rows, int32_t max_blocks_per_row,
+                                 int32_t tile_tokens, int32_t num_cus, nanocp_plan** out) {
+  if (!desc || !out || (num_shards > 0 && !shards)) return NANOCP_EINVAL;
+  *out = nullptr;
+  if (num_shards < 0 || num_q_rows < 0 || num_bt_rows < 0 || max_blocks_per_row < 0 || tile_tokens < 0 || num_cus < 0)
+    return NANOCP_EINVAL;
+  nanocp_status st = check_desc(*desc);
+  if (st != NANOCP_OK) return st;
+  const int ps = desc->page_size;
+  const int64_t row_tokens = (int64_t)max_blocks_per_row * ps;
+  for (int s = 0; s < num_shards; ++s) {
+    const nanocp_shard& sh = shards[s];
+    if (sh.kv_begin < 0 || sh.kv_end < sh.kv_begin) return NANOCP_EINVAL;
+    if (sh.q_row < 0 || sh.q_row >= num_q_rows || sh.bt_row < 0 || sh.bt_row >= num_bt_rows) return NANOCP_EBOUNDS;
+    if ((int64_t)sh.kv_end > row_tokens) return NANOCP_EBOUNDS;
+  }
+  if (num_cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return NANOCP_EHIP;
+    num_cus = prop.multiProcessorCount;
+  }
+
+  nanocp_plan* p = new (std::nothrow) nanocp_plan();
+  if (!p) return NANOCP_ENOMEM;
+  try {
+    p->desc = *desc;
+    p->num_shards = num_shards;
+    p->num_q_rows = num_q_rows;
+    p->num_bt_rows = num_bt_rows;
+    p->max_blocks = max_blocks_per_row;
+    p->variant = pick_variant(*desc);
+    const int Hkv = desc->num_kv_heads;
+    const int G = desc->num_q_heads / Hkv;
+    const int c0 = kTileOverheadPages;
+
+    // total cost in page units
+    int64_t units = 0;
+    for (int s = 0; s < num_shards; ++s) {
+      const nanocp_shard& sh = shards[s];
+      if (sh.kv_end == sh.kv_begin) continue;
+      const int64_t np = (sh.kv_end - 1) / ps - sh.kv_begin / ps + 1;
+      units += (np + c0) * Hkv;
+    }
+    const int64_t target_chunks = std::max<int64_t>(1, (int64_t)num_cus * workgroups_per_cu(p->variant));
+    int64_t cap;
+    const bool fixed = tile_tokens > 0;
+    if (fixed) {
+      cap = std::max<int64_t>(1, tile_tokens / ps) + c0;
+    } else {
+      cap = std::max<int64_t>((units + target_chunks - 1) / target_chunks, c0 + 4);
+    }
+
+    for (int attempt = 0;; ++attempt) {
+      p->tiles.clear();
+      int chunk = 0;
+      int64_t used = 0;
+      for (int s = 0; s < num_shards; ++s) {
+        const nanocp_shard& sh = shards[s];
+        if (sh.kv_end == sh.kv_begin) continue;
+        const int pb = sh.kv_begin / ps, pe = (sh.kv_end - 1) / ps + 1;
+        for (int h = 0; h < Hkv; ++h) {
+          int pg = pb;
+          while (pg < pe) {
+            if (used > 0 && cap - used < c0 + 1) {
+              ++chunk;
+              used = 0;
+            }
+            const int take = (int)std::min<int64_t>(pe - pg, cap - used - c0);
+            nanocp_tile t;
+            t.shard = s;
+            t.kv_head = h;
+            t.q_row = sh.q_row;
+            t.bt_row = sh.bt_row;
+            t.tok_begin = std::max(sh.kv_begin, pg * ps);
+            t.tok_end = std::min(sh.kv_end, (pg + take) * ps);
+            t.dst = -1;
+            t.chunk = chunk;
+            p->tiles.push_back(t);
+            used += c0 + take;
+            pg += take;
+          }
+        }
+      }
+      p->num_chunks = p->tiles.empty() ? 0 : chunk + 1;
+      if (fixed || p->num_chunks <= target_chunks || attempt > 64) break;
+      cap += std::max<int64_t>(1, cap / 64);
+    }
+
+    // chunk offsets
+    p->chunk_offsets.assign(p->num_chunks + 1, 0);
+    for (const nanocp_tile& t : p->tiles) p->chunk_offsets[t.chunk + 1]++;
+    for (int c = 0; c < p->num_chunks; ++c) p->chunk_offsets[c + 1] += p->chunk_offsets[c];
+
+    // partial slots and reduction segments: tiles of one (shard, head) are consecutive in the list
+    p->num_slots = 0;
+    size_t i = 0;
+    int next_shard = 0;
+    auto add_empty = [&](int upto) {
+      for (; next_shard < upto; ++next_shard)
+        if (shards[next_shard].kv_end == shards[next_shard].kv_begin)
+          for (int h = 0; h < Hkv; ++h) p->segs.push_back(Seg{next_shard, h, 0, 0});
+    };
+    while (i < p->tiles.size()) {
+      size_t j = i;
+      while (j < p->tiles.size() && p->tiles[j].shard == p->tiles[i].shard && p->tiles[j].kv_head == p->tiles[i].kv_head) ++j;
+      add_empty(p->tiles[i].shard);
+      if (j - i > 1) {
+        p->segs.push_back(Seg{p->tiles[i].shard, p->tiles[i].kv_head, p->num_slots, (int32_t)(j - i)});
+        for (size_t k = i; k < j; ++k) p->tiles[k].dst = p->num_slots++;
+      }
+      i = j;
+    }
+    add_empty(num_shards);
+    // workspace: o partials [slots, G, Dv] then lse partials [slots, G], each 256-byte aligned
+    const size_t o_bytes = ((size_t)p->num_slots * G * desc->head_dim_v * sizeof(float) + 255) & ~(size_t)255;
+    const size_t l_bytes = ((size_t)p->num_slots * G * sizeof(float) + 255) & ~(size_t)255;
+    p->workspace_bytes = p->num_slots ? o_bytes + l_bytes : 0;
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return NANOCP_ENOMEM;
+  }
+  *out = p;
+  return NANOCP_OK;
+}
+
+nanocp_status nanocp_plan_query(const nanocp_plan* plan, int32_t* num_tiles, int32_t* num_chunks,
+                                size_t* workspace_bytes) {
+  if (!plan) return NANOCP_EINVAL;
+  if (num_tiles) *num_tiles = (int32_t)plan->tiles.size();
+  if (num_chunks) *num_chunks = plan->num_chunks;
+  if (workspace_bytes) *workspace_bytes = plan->workspace_bytes;
+  return NANOCP_OK;
+}
+
+nanocp_status nanocp_plan_tiles(const nanocp_plan* plan, const nanocp_tile** tiles, int32_t* num_tiles) {
+  if (!plan || !tiles || !num_tiles) return NANOCP_EINVAL;
+  *tiles = plan->tiles.data();
+  *num_tiles = (int32_t)plan->tiles.size();
+  return NANOCP_OK;
+}
+
+const char* nanocp_plan_kernel(const nanocp_plan* plan) {
+  if (!plan) return "";
+  switch (plan->variant) {
+    case kGqaMfmaBf16: return "gqa_mfma_bf16";
+    case kGqaMfmaFp8: return "gqa_mfma_fp8";
+    case kMlaMfmaBf16: return "mla_mfma_bf16";
+    default: return "generic";
+  }
+}
+
+nanocp_status nanocp_plan_upload(nanocp_plan* plan, void* stream) {
+  if (!plan) return NANOCP_EINVAL;
+  if (plan->device >= 0) return NANOCP_ESTATE;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return NANOCP_EHIP;
+  hipStream_t st = (hipStream_t)stream;
+  auto up = [&](void** dptr, const void* src, size_t bytes) -> nanocp_status {
+    if (bytes == 0) return NANOCP_OK;
+    if (hipMalloc(dptr, bytes) != hipSuccess) return NANOCP_ENOMEM;
+    if (hipMemcpyAsync(*dptr, src, bytes, hipMemcpyHostToDevice, st) != hipSuccess) return NANOCP_EHIP;
+    return NANOCP_OK;
+  };
+  nanocp_status s;
+  if ((s = up((void**)&plan->d_tiles, plan->tiles.data(), plan->tiles.size() * sizeof(nanocp_tile))) != NANOCP_OK) return s;
+  if ((s = up((void**)&plan->d_chunk_offsets, plan->chunk_offsets.data(), plan->chunk_offsets.size() * sizeof(int32_t))) != NANOCP_OK) return s;
+  if ((s = up((void**)&plan->d_segs, plan->segs.data(), plan->segs.size() * sizeof(Seg))) != NANOCP_OK) return s;
+  // the host vectors must outlive the async copies: they live as long as the plan, and destroy synchronises
+  plan->device = dev;
+  return NANOCP_OK;
+}
+
+void nanocp_plan_destroy(nanocp_plan* plan) {
+  if (!plan) return;
+  if (plan->device >= 0) {
+    (void)hipDeviceSynchronize();
+    if (plan->d_tiles) (void)hipFree(plan->d_tiles);
+    if (plan->d_chunk_offsets) (void)hipFree(plan->d_chunk_offsets);
+    if (plan->d_segs) (void)hipFree(plan->d_segs);
+  }
+  delete plan;
+}
+
+const char* nanocp_status_str(nanocp_status s) {
+  switch (s) {
+    case NANOCP_OK: return "ok";
+    case NANOCP_EINVAL: return "invalid argument";
+    case NANOCP_ESHAPE: return "inconsistent shape";
+    case NANOCP_EBOUNDS: return "out of bounds";
+    case NANOCP_EUNSUPPORTED: return "unsupported configuration";
+    case NANOCP_ENOMEM: return "out of memory";
+    case NANOCP_EHIP: return "HIP runtime error";
+    case NANOCP_ESTATE: return "plan in wrong state";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

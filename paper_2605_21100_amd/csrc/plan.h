@@ -1,0 +1,60 @@
+// Internal definitions shared by the host planner, the launchers and the kernels.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "nanocp.h"
+
+namespace nanocp {
+
+enum Variant : int32_t { kGeneric = 0, kGqaMfmaBf16 = 1, kGqaMfmaFp8 = 2, kMlaMfmaBf16 = 3 };
+
+// Reduction segment: the tile partials of one (shard, kv head).  Only segments with
+// n_parts != 1 exist (0 parts = empty shard, filled with O = 0 / LSE = -inf).
+struct Seg {
+  int32_t shard;
+  int32_t kv_head;
+  int32_t slot_begin;
+  int32_t n_parts;
+};
+
+constexpr int kThreads = 256;       // every kernel here runs 4 wavefronts per workgroup
+constexpr int kTileOverheadPages = 1;  // cost charged per tile for Q load, combine and write-back
+
+// Arguments of the tile kernels (passed by value).
+struct KParams {
+  const void* q;
+  const void* k_pool;
+  const void* v_pool;
+  const float* k_scale;
+  const float* v_scale;
+  const int32_t* block_table;
+  float* out_o;
+  float* out_lse;
+  float* ws_o;    // [num_slots, G, Dv]
+  float* ws_lse;  // [num_slots, G]
+  const nanocp_tile* tiles;
+  const int32_t* chunk_offsets;
+  uint64_t* tile_clock;  // may be null
+  int32_t Hq, Hkv, G, Dk, Dv, ps, max_blocks, kind;
+  float scale;
+};
+
+}  // namespace nanocp
+
+struct nanocp_plan {
+  nanocp_attn_desc desc;
+  int32_t num_shards, num_q_rows, num_bt_rows, max_blocks;
+  int32_t variant;
+  int32_t num_chunks;
+  int32_t num_slots;
+  size_t workspace_bytes;
+  std::vector<nanocp_tile> tiles;       // grouped by chunk, in execution order
+  std::vector<int32_t> chunk_offsets;   // [num_chunks + 1]
+  std::vector<nanocp::Seg> segs;
+  // device copy
+  int device = -1;
+  nanocp_tile* d_tiles = nullptr;
+  int32_t* d_chunk_offsets = nullptr;
+  nanocp::Seg* d_segs = nullptr;
+};

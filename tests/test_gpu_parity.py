@@ -1,0 +1,240 @@
+"""GPU parity: the HIP path, called through the C ABI, against the float64 checker element by element
+on the same seeded inputs (reduced configs spanning several tiles and ragged tails, several tilings),
+the Phase-4 merge against exact unsharded attention, the GPU's merged result against its own
+unsharded run, edge cases, and sampled outputs at the full benchmark sizes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_21100_amd as nanocp
+import workloads as W
+from parity import MERGE_VS_UNSHARDED_ABS, check_output
+
+pytestmark = pytest.mark.gpu
+
+EXPECTED_KERNEL = {1: "generic", 2: "gqa_mfma_bf16", 3: "gqa_mfma_bf16", 5: "gqa_mfma_fp8"}
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _merge_on_gpu(db, o_parts, lse_parts, out_dtype=torch.float32):
+    b = db.batch
+    R = b.num_requests
+    d = b.desc
+    out = torch.empty((R, d.num_q_heads, d.head_dim_v), dtype=out_dtype, device="cuda")
+    out_lse = torch.empty((R, d.num_q_heads), dtype=torch.float32, device="cuda")
+    po = torch.from_numpy(b.part_offsets).cuda()
+    pi = torch.from_numpy(b.part_index).cuda()
+    nanocp.nanocp_merge_partials(db.desc, o_parts, lse_parts, po, pi, R, out, out_lse)
+    torch.cuda.synchronize()
+    return out, out_lse
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("tile_tokens", [0, 128, 448])
+def test_partial_and_merge_match_oracle(cid, tile_tokens):
+    _say(f"[case] reduced config {cid} tile_tokens {tile_tokens}")
+    b = W.reduced(cid)
+    ps = b.desc.page_size
+    tt = 0 if tile_tokens == 0 else max(ps, tile_tokens // ps * ps)
+    db = nanocp.DeviceBatch(b, tile_tokens=tt)
+    if cid in EXPECTED_KERNEL:
+        assert db.plan.kernel == EXPECTED_KERNEL[cid]
+    if tt:
+        assert (db.plan.tiles()["dst"] >= 0).any()          # the tiling really splits shards
+    o, lse = db.partial()
+    torch.cuda.synchronize()
+    ref_o, ref_lse = oracle.local_partials(b)
+    check_output(b.desc, o.cpu().numpy(), lse.cpu().numpy(), ref_o, ref_lse, f"c{cid} partial")
+
+    # Phase 4: local partials (GPU) + remote partials (checker, rounded to f32) -> exact attention
+    rem_o, rem_lse = oracle.remote_partials(b)
+    parts_o = torch.cat([o, torch.from_numpy(rem_o.astype(np.float32)).cuda()])
+    parts_lse = torch.cat([lse, torch.from_numpy(rem_lse.astype(np.float32)).cuda()])
+    out, out_lse = _merge_on_gpu(db, parts_o, parts_lse)
+    ref_m, ref_mlse = oracle.merge_requests(np.concatenate([ref_o, rem_o]), np.concatenate([ref_lse, rem_lse]),
+                                            b.part_offsets, b.part_index)
+    check_output(b.desc, out.cpu().numpy(), out_lse.cpu().numpy(), ref_m, ref_mlse, f"c{cid} merged")
+    for r in [r for r in range(b.num_requests) if b.cp_degree[r] > 1][:3]:
+        full_o, full_lse = oracle.request_full_attention(b, r)
+        check_output(b.desc, out[r].cpu().numpy(), out_lse[r].cpu().numpy(), full_o, full_lse, f"c{cid} req {r} vs full")
+    # bf16 output epilogue: same values rounded once
+    out16, _ = _merge_on_gpu(db, parts_o, parts_lse, torch.bfloat16)
+    assert torch.equal(out16, out.to(torch.bfloat16))
+    db.plan.close()
+
+
+@pytest.mark.parametrize("cid", [1, 3, 4, 5])
+def test_merged_equals_gpu_unsharded(cid):
+    """The GPU's merge of its own d partials against the GPU's own single-shard run of the same request."""
+    _say(f"[case] merged vs unsharded, reduced config {cid}")
+    b = W.reduced(cid, hold_all=True) if cid in (3, 5) else W.reduced(cid)
+    assert len(b.remote_meta) == 0
+    db = nanocp.DeviceBatch(b, tile_tokens=256 if b.desc.page_size <= 64 else 0)
+    o, lse = db.partial()
+    out, out_lse = _merge_on_gpu(db, o, lse)
+    # unsharded: one shard per request covering all its tokens, on the same pools / block table
+    whole = []
+    for r in range(b.num_requests):
+        idx = b.part_index[b.part_offsets[r]:b.part_offsets[r + 1]]
+        sh = b.shards[idx]
+        assert len(set(sh[:, 1].tolist())) == 1
+        whole.append([r, sh[0, 1], sh[:, 2].min(), sh[:, 3].max()])
+    whole = np.asarray(whole, np.int32)
+    plan = nanocp.Plan(db.desc, whole, b.q.shape[0], b.block_table.shape[0], b.block_table.shape[1]).upload()
+    d = b.desc
+    uo = torch.empty((len(whole), d.num_q_heads, d.head_dim_v), dtype=torch.float32, device="cuda")
+    ul = torch.empty((len(whole), d.num_q_heads), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+    nanocp.nanocp_decode_attn_partial(plan, db.q, db.k_pool, db.v_pool, db.k_scale, db.v_scale, db.block_table,
+                                      uo, ul, ws)
+    torch.cuda.synchronize()
+    split = [r for r in range(b.num_requests) if b.cp_degree[r] > 1]
+    assert split
+    err = (out[split] - uo[split]).abs().max().item()
+    lerr = (out_lse[split] - ul[split]).abs().max().item()
+    _say(f"    merged vs unsharded: max abs {err:.3e}, LSE {lerr:.3e}")
+    assert err <= MERGE_VS_UNSHARDED_ABS and lerr <= MERGE_VS_UNSHARDED_ABS
+    plan.close()
+    db.plan.close()
+
+
+def _edge_batch(kv_dtype, shards_spec, seed=77):
+    """Hand-made shard ranges on one row per shard (GQA 64/4x128, page 64; f32 uses the small C1 shape)."""
+    rng = np.random.default_rng(seed)
+    if kv_dtype == "f32":
+        desc = W.AttnDesc("gqa", "f32", "f32", 8, 2, 64, 64, 16, 0.125)
+    else:
+        desc = W.AttnDesc("gqa", "bf16", kv_dtype, 64, 4, 128, 128, 64, 128 ** -0.5)
+    lengths = [max(e, 1) for (_, e) in shards_spec]
+    ranges = [[(0, L)] for L in lengths]
+    b = W.build_batch("edge", seed, desc, lengths, ranges, [[0]] * len(lengths), rng)
+    for i, (bg, en) in enumerate(shards_spec):           # narrow each shard to the requested range
+        b.shards[i, 2], b.shards[i, 3] = bg, en
+    return b
+
+
+@pytest.mark.parametrize("kv_dtype", ["f32", "bf16", "fp8"])
+def test_edge_ranges(kv_dtype):
+    """Empty shard, single token, ranges inside one page, starting / ending mid-page, exact page multiples."""
+    _say(f"[case] edge ranges {kv_dtype}")
+    ps = 16 if kv_dtype == "f32" else 64
+    spec = [(0, 0), (0, 1), (5, 6), (3, ps - 2), (ps - 1, ps + 1), (0, ps), (0, 4 * ps), (7, 5 * ps + 9),
+            (2 * ps, 2 * ps), (ps + 1, 3 * ps), (0, 33), (31, 33), (32, 64 if ps == 64 else 48), (0, 9 * ps + 1)]
+    b = _edge_batch(kv_dtype, spec)
+    for tt in (0, ps, 2 * ps):
+        db = nanocp.DeviceBatch(b, tile_tokens=tt)
+        o, lse = db.partial()
+        torch.cuda.synchronize()
+        ref_o, ref_lse = oracle.local_partials(b)
+        check_output(b.desc, o.cpu().numpy(), lse.cpu().numpy(), ref_o, ref_lse, f"edge {kv_dtype} tt={tt}")
+        assert torch.all(o[0] == 0) and torch.all(torch.isneginf(lse[0]))
+        db.plan.close()
+
+
+def test_merge_edge_cases():
+    """All-empty merge, identity (one part), parts ignored when LSE = -inf even if their output is NaN."""
+    _say("[case] merge edge cases")
+    desc = nanocp.make_desc("gqa", "bf16", "bf16", 8, 2, 64, 64, 64, 0.1)
+    rng = np.random.default_rng(3)
+    o = rng.standard_normal((5, 8, 64)).astype(np.float32)
+    lse = rng.standard_normal((5, 8)).astype(np.float32)
+    lse[3] = -np.inf
+    o[3] = np.nan
+    lse[4] = -np.inf
+    offs = np.array([0, 1, 4, 5, 5, 7], np.int32)            # r0: {0}; r1: {1,2,3}; r2: {4} all empty; r3: none; r4: {0,1}
+    idx = np.array([0, 1, 2, 3, 4, 0, 1], np.int32)
+    R = 5
+    out = torch.empty((R, 8, 64), device="cuda")
+    out_lse = torch.empty((R, 8), device="cuda")
+    nanocp.nanocp_merge_partials(desc, torch.from_numpy(o).cuda(), torch.from_numpy(lse).cuda(),
+                                 torch.from_numpy(offs).cuda(), torch.from_numpy(idx).cuda(), R, out, out_lse)
+    torch.cuda.synchronize()
+    o64 = np.where(np.isnan(o), 0.0, o).astype(np.float64)
+    ref_o, ref_lse = oracle.merge_requests(o64, lse.astype(np.float64), offs, idx)
+    got = out.cpu().numpy()
+    assert not np.isnan(got).any()
+    np.testing.assert_allclose(got, ref_o, atol=1e-6)
+    gl = out_lse.cpu().numpy()
+    assert np.array_equal(np.isneginf(gl), np.isneginf(ref_lse))
+    np.testing.assert_allclose(gl[np.isfinite(ref_lse)], ref_lse[np.isfinite(ref_lse)], atol=1e-6)
+    assert np.array_equal(got[0], o[0])                          # single part: identity
+    # identity part_index (NULL)
+    offs2 = np.array([0, 2, 3], np.int32)
+    out2 = torch.empty((2, 8, 64), device="cuda")
+    nanocp.nanocp_merge_partials(desc, torch.from_numpy(o[:3]).cuda(), torch.from_numpy(lse[:3]).cuda(),
+                                 torch.from_numpy(offs2).cuda(), None, 2, out2, None)
+    torch.cuda.synchronize()
+    r2, _ = oracle.merge_requests(o64[:3], lse[:3].astype(np.float64), offs2, np.arange(3))
+    np.testing.assert_allclose(out2.cpu().numpy(), r2, atol=1e-6)
+
+
+def test_device_call_errors():
+    _say("[case] device call errors")
+    b = W.reduced(2)
+    db = nanocp.DeviceBatch(b, tile_tokens=128)
+    assert db.plan.workspace_bytes > 0
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(nanocp.NanocpError) as e:
+        nanocp.nanocp_decode_attn_partial(db.plan, db.q, db.k_pool, db.v_pool, None, None, db.block_table,
+                                          db.out_o, db.out_lse, small)
+    assert e.value.status == nanocp.EBOUNDS
+    with pytest.raises(nanocp.NanocpError) as e:
+        nanocp.nanocp_decode_attn_partial(db.plan, None, db.k_pool, db.v_pool, None, None, db.block_table,
+                                          db.out_o, db.out_lse, db.workspace)
+    assert e.value.status == nanocp.EINVAL
+    fresh = nanocp.Plan(db.desc, b.shards, b.q.shape[0], b.block_table.shape[0], b.block_table.shape[1])
+    with pytest.raises(nanocp.NanocpError) as e:
+        nanocp.nanocp_decode_attn_partial(fresh, db.q, db.k_pool, db.v_pool, None, None, db.block_table,
+                                          db.out_o, db.out_lse, db.workspace)
+    assert e.value.status == nanocp.ESTATE
+    fresh.close()
+    db.plan.close()
+
+
+def test_run_to_run_determinism():
+    _say("[case] determinism")
+    b = W.reduced(3)
+    db = nanocp.DeviceBatch(b)
+    o1, l1 = (t.clone() for t in db.partial())
+    o2, l2 = db.partial()
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(l1, l2)
+    db.plan.close()
+
+
+def _sample_shards(b, k, rng):
+    lens = b.shards[:, 3] - b.shards[:, 2]
+    order = np.argsort(lens)
+    pick = {int(order[-1]), int(order[0]), int(order[len(order) // 2])}
+    pick |= set(int(i) for i in rng.choice(len(lens), size=min(k, len(lens)), replace=False))
+    return sorted(pick)
+
+
+@pytest.mark.parametrize("cid", [2, 3, 5])
+def test_full_size_sampled(cid):
+    """Full benchmark sizes in the launch configuration bench.py times (automatic tiling): sampled shard
+    entries, always including the longest, checked one by one; every output finite."""
+    _say(f"[case] full-size config {cid}, sampled shards")
+    b = W.FULL[cid](with_remote_kv=False)
+    db = nanocp.DeviceBatch(b)
+    assert db.plan.kernel == EXPECTED_KERNEL[cid]
+    o, lse = db.partial()
+    torch.cuda.synchronize()
+    assert torch.isfinite(o).all() and torch.isfinite(lse).all()
+    rng = np.random.default_rng(cid)
+    for s in _sample_shards(b, 4, rng):
+        _say(f"    shard {s}: tokens {int(b.shards[s, 3] - b.shards[s, 2])}")
+        ro, rl = oracle.attn_partial_paged(b.desc, b.q, b.k_pool, b.v_pool, b.k_scale, b.v_scale,
+                                           b.block_table, b.shards[s])
+        check_output(b.desc, o[s].cpu().numpy(), lse[s].cpu().numpy(), ro, rl, f"c{cid} full shard {s}")
+    # split invariance at full size: LSE of a split request's merge is insensitive to the tiling used
+    db2 = nanocp.DeviceBatch(b, tile_tokens=1024)
+    o2, lse2 = db2.partial()
+    torch.cuda.synchronize()
+    assert (o2 - o).abs().max().item() <= 1e-5 and (lse2 - lse).abs().max().item() <= 1e-5
+    db.plan.close()
+    db2.plan.close()

@@ -1,0 +1,167 @@
+"""Host-side checks: the library loads and exports the declared C ABI; the planner's work-list is a
+valid, balanced partition (coverage, page-aligned cuts, slots, chunk cost); argument errors map to codes.
+No GPU is touched: plans are built with an explicit compute-unit count."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2605_21100_amd as nanocp
+import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "nanocp.h")).read()
+    declared = sorted(set(re.findall(r"\b(nanocp_[a-z_]+)\s*\(", hdr)))
+    assert set(declared) == set(nanocp.EXPORTS)
+    lib = ctypes.CDLL(nanocp.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert ctypes.sizeof(nanocp.AttnDesc) == 36 and ctypes.sizeof(nanocp.Shard) == 16
+    assert ctypes.sizeof(nanocp.Tile) == 32
+
+
+def _plan(batch, tile_tokens=0, num_cus=256):
+    return nanocp.Plan(nanocp.desc_from(batch.desc), batch.shards, batch.q.shape[0],
+                       batch.block_table.shape[0], batch.block_table.shape[1], tile_tokens, num_cus)
+
+
+def _check_partition(batch, plan, tile_tokens):
+    d = batch.desc
+    ps = d.page_size
+    tiles = plan.tiles()
+    assert len(tiles) == plan.num_tiles
+    # chunks are numbered consecutively in list order
+    assert np.all(np.diff(tiles["chunk"]) >= 0) and (len(tiles) == 0 or tiles["chunk"][-1] == plan.num_chunks - 1)
+    per = {}
+    for t in tiles:
+        per.setdefault((int(t["shard"]), int(t["kv_head"])), []).append(t)
+    slots = []
+    for s, (q_row, bt_row, b, e) in enumerate(batch.shards):
+        for h in range(d.num_kv_heads):
+            ts = per.get((s, h), [])
+            if e == b:
+                assert not ts
+                continue
+            assert ts[0]["tok_begin"] == b and ts[-1]["tok_end"] == e
+            for a, c in zip(ts[:-1], ts[1:]):
+                assert a["tok_end"] == c["tok_begin"] and a["tok_end"] % ps == 0     # page-aligned cuts
+            for t in ts:
+                assert t["tok_end"] > t["tok_begin"] and t["q_row"] == q_row and t["bt_row"] == bt_row
+                assert (t["dst"] == -1) == (len(ts) == 1)
+            if len(ts) > 1:
+                ds = [int(t["dst"]) for t in ts]
+                assert ds == list(range(ds[0], ds[0] + len(ts)))
+                slots += ds
+    assert sorted(slots) == list(range(len(slots)))
+    G = d.num_q_heads // d.num_kv_heads
+    if slots:
+        assert plan.workspace_bytes >= len(slots) * G * (d.head_dim_v + 1) * 4
+    else:
+        assert plan.workspace_bytes == 0
+    # cost per chunk (pages + 1 per tile) never exceeds the cap implied by the request
+    cost = np.zeros(plan.num_chunks, np.int64)
+    for t in tiles:
+        cost[t["chunk"]] += (t["tok_end"] - 1) // ps - t["tok_begin"] // ps + 1 + 1
+    return cost
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("tile_tokens", [0, 64, 256, 1024])
+def test_plan_partitions_reduced_configs(cid, tile_tokens):
+    b = W.reduced(cid, with_remote_kv=False)
+    if tile_tokens and tile_tokens < b.desc.page_size:
+        tile_tokens = b.desc.page_size
+    plan = _plan(b, tile_tokens)
+    cost = _check_partition(b, plan, tile_tokens)
+    if tile_tokens:
+        assert cost.max() <= tile_tokens // b.desc.page_size + 1
+    else:
+        assert plan.num_chunks <= 512
+    plan.close()
+
+
+def test_auto_plan_balances_a_long_shard():
+    # one very long shard among short ones: its pages must be spread over many workgroups, and the
+    # chunk costs must be near-equal (the balance objective)
+    desc = W.AttnDesc("gqa", "bf16", "bf16", 64, 4, 128, 128, 64, 0.1)
+    lens = [131072] + [700] * 100
+    shards = np.array([[i, i, 0, L] for i, L in enumerate(lens)], np.int32)
+    plan = nanocp.Plan(nanocp.desc_from(desc), shards, len(lens), len(lens), 2048, 0, 256)
+    tiles = plan.tiles()
+    assert plan.num_chunks <= 512 and plan.num_chunks >= 480
+    long_chunks = np.unique(tiles["chunk"][tiles["shard"] == 0])
+    assert len(long_chunks) > 0.6 * plan.num_chunks            # 88 % of the bytes -> most workgroups
+    cost = np.zeros(plan.num_chunks, np.int64)
+    for t in tiles:
+        cost[t["chunk"]] += (t["tok_end"] - 1) // 64 - t["tok_begin"] // 64 + 2
+    assert cost[:-1].max() <= 1.1 * cost[:-1].mean() + 2
+    assert plan.kernel == "gqa_mfma_bf16"
+
+
+def test_kernel_selection():
+    def k(**kw):
+        base = dict(kind="gqa", q_dtype="bf16", kv_dtype="bf16", num_q_heads=64, num_kv_heads=4,
+                    head_dim_qk=128, head_dim_v=128, page_size=64, softmax_scale=0.1)
+        base.update(kw)
+        p = nanocp.Plan(nanocp.make_desc(**base), np.array([[0, 0, 0, 10]], np.int32), 1, 1, 4, 0, 8)
+        name = p.kernel
+        p.close()
+        return name
+    assert k() == "gqa_mfma_bf16"
+    assert k(kv_dtype="fp8") == "gqa_mfma_fp8"
+    assert k(num_q_heads=32) == "generic"
+    assert k(q_dtype="f32", kv_dtype="f32", page_size=16) == "generic"
+    assert k(kind="mla", num_q_heads=128, num_kv_heads=1, head_dim_qk=576, head_dim_v=512) in ("generic", "mla_mfma_bf16")
+
+
+def test_argument_errors():
+    d = nanocp.make_desc("gqa", "bf16", "bf16", 64, 4, 128, 128, 64, 0.1)
+    sh = np.array([[0, 0, 0, 10]], np.int32)
+
+    def status(desc=d, shards=sh, q_rows=1, bt_rows=1, max_blocks=4, tile=0, cus=8):
+        with pytest.raises(nanocp.NanocpError) as e:
+            nanocp.Plan(desc, shards, q_rows, bt_rows, max_blocks, tile, cus)
+        return e.value.status
+    assert status(shards=np.array([[0, 0, 5, 4]], np.int32)) == nanocp.EINVAL          # kv_end < kv_begin
+    assert status(shards=np.array([[0, 0, -1, 4]], np.int32)) == nanocp.EINVAL
+    assert status(shards=np.array([[1, 0, 0, 4]], np.int32)) == nanocp.EBOUNDS         # q_row out of range
+    assert status(shards=np.array([[0, 2, 0, 4]], np.int32)) == nanocp.EBOUNDS         # bt_row out of range
+    assert status(shards=np.array([[0, 0, 0, 257]], np.int32)) == nanocp.EBOUNDS       # beyond max_blocks*ps
+    assert status(desc=nanocp.make_desc("gqa", "bf16", "bf16", 64, 5, 128, 128, 64, 0.1)) == nanocp.ESHAPE
+    assert status(desc=nanocp.make_desc("gqa", "bf16", "bf16", 64, 4, 100, 128, 64, 0.1)) == nanocp.ESHAPE
+    assert status(desc=nanocp.make_desc("mla", "bf16", "bf16", 64, 4, 576, 512, 64, 0.1)) == nanocp.ESHAPE
+    assert status(desc=nanocp.make_desc("gqa", "f32", "bf16", 64, 4, 128, 128, 64, 0.1)) == nanocp.EUNSUPPORTED
+    assert status(desc=nanocp.make_desc("gqa", "bf16", "bf16", 64, 4, 1024, 128, 64, 0.1)) == nanocp.EUNSUPPORTED
+    assert status(desc=nanocp.make_desc(7, "bf16", "bf16", 64, 4, 128, 128, 64, 0.1)) == nanocp.EINVAL
+    assert status(tile=-1) == nanocp.EINVAL
+    ok = nanocp.Plan(d, np.zeros((0, 4), np.int32), 0, 0, 0, 0, 8)                     # empty batch is legal
+    assert ok.num_tiles == 0 and ok.num_chunks == 0 and ok.workspace_bytes == 0
+    e = nanocp.Plan(d, np.array([[0, 0, 7, 7]], np.int32), 1, 1, 4, 0, 8)              # empty shard is legal
+    assert e.num_tiles == 0
+
+
+def test_full_size_plans_are_balanced():
+    for cid in (2, 3, 5):
+        b = W.FULL[cid](with_remote_kv=False) if cid != 2 else None
+        if b is None:
+            rng = np.random.default_rng(W.configs.BASE_SEED + 2)
+            lens = rng.integers(1024, 8193, size=64)
+            shards = np.array([[i, i, 0, L] for i, L in enumerate(lens)], np.int32)
+            desc = W.AttnDesc("gqa", "bf16", "bf16", 64, 4, 128, 128, 64, 0.1)
+            plan = nanocp.Plan(nanocp.desc_from(desc), shards, 64, 64, 128, 0, 256)
+        else:
+            plan = _plan(b)
+        tiles = plan.tiles()
+        cost = np.zeros(plan.num_chunks, np.int64)
+        for t in tiles:
+            cost[t["chunk"]] += (t["tok_end"] - 1) // 64 - t["tok_begin"] // 64 + 2
+        assert plan.num_chunks <= 512
+        assert cost[:-1].max() <= 1.05 * cost[:-1].mean() + 2, (cid, cost.max(), cost.mean())
+        n_partial = int((tiles["dst"] >= 0).sum())
+        assert n_partial <= 2 * plan.num_chunks
+        plan.close()

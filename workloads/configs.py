@@ -63,7 +63,7 @@ def config3_seed(num_requests=128, median=2048, sigma=1.2, lo=16, hi=131072, thr
 
 
 def config3(seed=None, num_requests=128, median=2048, sigma=1.2, lo=16, hi=131072,
-            threshold=CP_THRESHOLD, with_remote_kv=True):
+            threshold=CP_THRESHOLD, with_remote_kv=True, hold_all=False):
     """Mixed long-tail DCP batch: lognormal lengths; a request longer than `threshold` has
     CP degree d=min(8,ceil(len/threshold)); this GPU holds shard (request index mod d) of it."""
     if seed is None:
@@ -74,7 +74,7 @@ def config3(seed=None, num_requests=128, median=2048, sigma=1.2, lo=16, hi=13107
     for r, L in enumerate(lengths):
         d = _cp_degree(L, threshold)
         ranges.append(even_split(L, d))
-        local.append([r % d])
+        local.append(list(range(d)) if hold_all else [r % d])
     return build_batch("c3_mixed_dcp", seed, _gqa_desc(), lengths, ranges, local, rng, with_remote_kv)
 
 
@@ -96,7 +96,8 @@ def config4(seed=None, num_requests=64, lo=4096, hi=32768, with_remote_kv=True):
     return build_batch("c4_mla_bf16", seed, desc, lengths, ranges, local, rng, with_remote_kv)
 
 
-def config5(seed=None, long_len=1048576, cp=8, held=3, num_short=256, lo=512, hi=4096, with_remote_kv=True):
+def config5(seed=None, long_len=1048576, cp=8, held=3, num_short=256, lo=512, hi=4096, with_remote_kv=True,
+            hold_all=False):
     """fp8 KV: shard `held` of `cp` of one very long request co-batched with short local requests.
     Request 0 is the long one."""
     seed = BASE_SEED + 5 if seed is None else seed
@@ -104,26 +105,27 @@ def config5(seed=None, long_len=1048576, cp=8, held=3, num_short=256, lo=512, hi
     short = rng.integers(lo, hi + 1, size=num_short)
     lengths = np.concatenate([[long_len], short])
     ranges = [even_split(long_len, cp)] + [[(0, int(L))] for L in short]
-    local = [[held]] + [[0] for _ in short]
+    local = [list(range(cp)) if hold_all else [held]] + [[0] for _ in short]
     return build_batch("c5_fp8_long_shard", seed, _gqa_desc("fp8"), lengths, ranges, local, rng, with_remote_kv)
 
 
 FULL = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
 
 
-def reduced(config_id, with_remote_kv=True):
+def reduced(config_id, with_remote_kv=True, hold_all=False):
     """Same recipes at sizes the float64 checker handles in seconds, still spanning several
-    tiles, ragged tails and (for 3 and 5) a shard much longer than the rest."""
+    tiles, ragged tails and (for 3 and 5) a shard much longer than the rest.  hold_all (3 and 5):
+    every shard of a split request is local, so one GPU can also run the request unsharded."""
     if config_id == 1:
         return config1(with_remote_kv=with_remote_kv)
     if config_id == 2:
         return config2(num_requests=12, lo=100, hi=3000, with_remote_kv=with_remote_kv)
     if config_id == 3:
         return config3(num_requests=24, median=300, sigma=1.2, lo=16, hi=12000, threshold=3000,
-                       with_remote_kv=with_remote_kv)
+                       with_remote_kv=with_remote_kv, hold_all=hold_all)
     if config_id == 4:
         return config4(num_requests=6, lo=200, hi=1500, with_remote_kv=with_remote_kv)
     if config_id == 5:
         return config5(long_len=40000, cp=8, held=3, num_short=20, lo=50, hi=700,
-                       with_remote_kv=with_remote_kv)
+                       with_remote_kv=with_remote_kv, hold_all=hold_all)
     raise ValueError(config_id)
