@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the DCP decode-attention hot path on one MI355X.
+
+A step = one pass of the whole path over one synthetic batch already resident in HBM:
+    nanocp_decode_attn_partial (tile kernel + tile reduce)  ->  nanocp_merge_partials.
+The plan (host tile work-list) is built and uploaded once, outside the timed region, as the paper
+amortises scheduling over decode iterations.  Default workload: config 3, the mixed long-tail DCP
+batch the headline metric is quoted on.  Successive steps alternate between two copies of the KV
+pools so that no step can be served from the 256 MB last-level cache.
+
+Prints ONE JSON line (last line of stdout).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+METRIC = "decode-attention KV GB/s (% of HBM peak) + µs/step, mixed ragged DCP batch"
+WORKLOAD_NAMES = {1: "config1: tiny fp32 GQA", 2: "config2: bf16 GQA 64 local requests U[1024,8192]",
+                  3: "config3: mixed long-tail DCP batch, 128 requests lognormal(median 2048, sigma 1.2), bf16 GQA 64q/4kv d128",
+                  4: "config4: MLA-absorbed bf16, 128 heads, 576/512, 64 requests U[4096,32768], half split CP=2",
+                  5: "config5: fp8 KV, 131072-token shard (CP=8 of 1,048,576) + 256 short requests"}
+
+
+def cpu_baseline(batch, budget_s=20.0):
+    """Time the float64 checker (as it stands) on a bounded sample of the same workload's shard entries."""
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    lens = batch.shards[:, 3] - batch.shards[:, 2]
+    order = np.argsort(-lens)            # longest first: the sample keeps the workload's long tail
+    done_bytes, done_tokens, picked = 0, 0, 0
+    t0 = time.perf_counter()
+    for s in order:
+        oracle.attn_partial_paged(batch.desc, batch.q, batch.k_pool, batch.v_pool, batch.k_scale, batch.v_scale,
+                                  batch.block_table, batch.shards[s])
+        done_tokens += int(lens[s])
+        picked += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    done_bytes = done_tokens * batch.desc.kv_bytes_per_token
+    return {"value": done_bytes / dt / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{picked} longest of {len(lens)} shard entries ({done_tokens} of {int(lens.sum())} tokens), "
+                      f"{dt:.1f} s, float64 numpy partial attention"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--tile-tokens", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-straggle", action="store_true")
+    ap.add_argument("--dump-tiles", default="", help="write the tile list and per-tile device clocks to this .npz")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain device copy of known size (1 GiB read + 1 GiB written per launch); "
+                         "used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of a DCP decode step; this build has no multi-GPU path "
+              "(--gpus must be 1).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2605_21100_amd as nanocp
+    import workloads as W
+
+    torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+        for a, b in evs:
+            a.record()
+            dst.copy_(src)
+            b.record()
+        torch.cuda.synchronize()
+        ms = np.array([a.elapsed_time(b) for a, b in evs])[2:]
+        print(json.dumps({"calibrate_copy_bytes_each_way": 1 << 30, "launches": 20, "ms_mean": float(ms.mean()),
+                          "read_plus_write_GBs": 2 * (1 << 30) / (ms.mean() * 1e-3) / 1e9}))
+        return
+    batch = W.FULL[args.config](with_remote_kv=False)
+    d = batch.desc
+    db = nanocp.DeviceBatch(batch, tile_tokens=args.tile_tokens)
+    pools = [(db.k_pool, db.v_pool, db.k_scale, db.v_scale)]
+    pools.append(tuple(None if t is None else t.clone() for t in pools[0]))
+    S, R = batch.num_shards, batch.num_requests
+    rem_o, rem_lse = W.synthetic_remote_partials(batch)
+    n_rem = rem_o.shape[0]
+    # pooled partial list: [local partials (written by the kernel) | remote partials (received)]
+    parts_o = torch.empty((S + n_rem, d.num_q_heads, d.head_dim_v), dtype=torch.float32, device="cuda")
+    parts_lse = torch.empty((S + n_rem, d.num_q_heads), dtype=torch.float32, device="cuda")
+    if n_rem:
+        parts_o[S:] = torch.from_numpy(rem_o).cuda()
+        parts_lse[S:] = torch.from_numpy(rem_lse).cuda()
+    part_offsets = torch.from_numpy(batch.part_offsets).cuda()
+    part_index = torch.from_numpy(batch.part_index).cuda()
+    out = torch.empty((R, d.num_q_heads, d.head_dim_v), dtype=torch.bfloat16 if d.q_dtype == "bf16" else torch.float32,
+                      device="cuda")
+    local_o, local_lse = parts_o[:S], parts_lse[:S]
+
+    def step(i, ev=None):
+        k, v, ks, vs = pools[i & 1]
+        if ev:
+            ev[0].record()
+        nanocp.nanocp_decode_attn_partial(db.plan, db.q, k, v, ks, vs, db.block_table, local_o, local_lse,
+                                          db.workspace)
+        if ev:
+            ev[1].record()
+        nanocp.nanocp_merge_partials(db.desc, parts_o, parts_lse, part_offsets, part_index, R, out)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # dominant kernel: the tile kernel inside nanocp_decode_attn_partial, timed with events on the launch stream
+    # (torch's current stream is the one handed to the library)
+    n_ev = min(args.steps, 100)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
+    for i in range(n_ev):
+        step(i, evs[i])
+    torch.cuda.synchronize()
+    part_ms = np.array([a.elapsed_time(b) for a, b in evs])
+    kv_bytes = batch.kv_bytes
+    achieved = kv_bytes / (part_ms.mean() * 1e-3) / 1e9
+
+    extra = {}
+    if not args.no_straggle:
+        clk = torch.zeros((max(db.plan.num_tiles, 1), 2), dtype=torch.int64, device="cuda")
+        for rep in range(3):
+            nanocp.nanocp_decode_attn_partial(db.plan, db.q, *[pools[rep & 1][j] for j in range(4)], db.block_table,
+                                              local_o, local_lse, db.workspace, tile_clock=clk)
+        torch.cuda.synchronize()
+        c = clk.cpu().numpy().astype(np.int64)
+        tiles = db.plan.tiles()
+        per_chunk_start = np.full(db.plan.num_chunks, np.iinfo(np.int64).max)
+        per_chunk_end = np.zeros(db.plan.num_chunks, np.int64)
+        np.minimum.at(per_chunk_start, tiles["chunk"], c[:, 0])
+        np.maximum.at(per_chunk_end, tiles["chunk"], c[:, 1])
+        if args.dump_tiles:
+            np.savez(args.dump_tiles, tiles=tiles, clock=c)
+        chunk_t = (per_chunk_end - per_chunk_start).astype(np.float64) / 100.0       # 100 MHz clock -> microseconds
+        span = (per_chunk_end.max() - per_chunk_start.min()) / 100.0
+        extra = {"chunks": int(db.plan.num_chunks), "tiles": int(db.plan.num_tiles),
+                 "chunk_time_us_mean": float(chunk_t.mean()), "chunk_time_us_max": float(chunk_t.max()),
+                 "straggle_max_over_mean": float(chunk_t.max() / chunk_t.mean()), "kernel_span_us": float(span)}
+
+    result = {
+        "metric": METRIC, "value": kv_bytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": {"f32": "f32", "bf16": "bf16", "fp8": "fp8_e4m3"}[d.kv_dtype], "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[args.config], "seed": int(batch.seed), "shard_entries": S,
+                   "requests": R, "local_kv_tokens": batch.local_tokens, "kv_bytes": kv_bytes,
+                   "remote_partials": int(n_rem), "kernel": db.plan.kernel, "us_per_step": ms_per_step * 1e3,
+                   "pct_of_hbm_peak": 100.0 * kv_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, **extra},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": db.plan.kernel, "launch_us_mean": float(part_ms.mean() * 1e3),
+                     "launch_us_min": float(part_ms.min() * 1e3),
+                     "note": "events bracket nanocp_decode_attn_partial = tile kernel + tile-reduce kernel"},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(batch)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

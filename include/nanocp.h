@@ -19,9 +19,14 @@
  *
  * Memory layouts.  x = 16 bytes / sizeof(kv element): 4 (f32), 8 (bf16), 16 (fp8).
  *   q            [num_q_rows, Hq, Dk]              q_dtype (f32 or bf16)
- *   GQA k_pool   [num_pages, Hkv, Dk/x, ps, x]     a page of one kv head is Dk/x runs of ps 16-byte
- *                                                  vectors; vector (c, t) holds dims [c*x, c*x+x) of token t
- *   GQA v_pool   [num_pages, Hkv, ps/x, Dv, x]     vector (u, c) holds dim c of tokens [u*x, u*x+x)
+ *   GQA k_pool   [num_pages, Hkv, ps/4x, Dk/x, 4x, x]  a page of one kv head is ps/4x groups of 4x token slots; a
+ *                                                  group is Dk/x runs of 4x 16-byte vectors, vector (c, w) holding
+ *                                                  dims [c*x, c*x+x) of the group's slot w
+ *   GQA v_pool   [num_pages, Hkv, ps/x, Dv, x]     vector (u, c) holds dim c of x tokens.  Token slots are taken
+ *                                                  in groups of 4x; slot w = 16b + 4g + i (i < 4, g < 4) of group n
+ *                                                  is element 4b + i of vector u = 4n + g.  (For f32 this is plain
+ *                                                  order; for bf16/fp8 it is the order in which the matrix cores
+ *                                                  produce the scores, see csrc/gqa_mfma.hip.)  ps % 4x == 0.
  *   MLA k_pool   [num_pages, ps, Dk]               one latent row per token; V = its first Dv dims; v_pool NULL
  *   k_scale, v_scale [num_pages, Hkv] float        fp8 only: value = e4m3(byte) * scale   (OCP E4M3FN)
  *   block_table  [num_bt_rows, max_blocks_per_row] int32 physical page ids; entries beyond a
@@ -44,7 +49,8 @@ extern "C" {
 typedef enum {
   NANOCP_OK = 0,
   NANOCP_EINVAL = 1,       /* null pointer, negative size, kv_end < kv_begin, bad enum */
-  NANOCP_ESHAPE = 2,       /* Hq not a multiple of Hkv, dims/page size not a multiple of x, MLA with Hkv != 1 */
+  NANOCP_ESHAPE = 2,       /* Hq not a multiple of Hkv, Dk not a multiple of x, GQA page size not a multiple of 4x,
+                              MLA with Hkv != 1 or Dv > Dk */
   NANOCP_EBOUNDS = 3,      /* shard range beyond max_blocks*ps, q_row/bt_row out of range, workspace too small */
   NANOCP_EUNSUPPORTED = 4, /* dtype combination or shape no compiled kernel handles */
   NANOCP_ENOMEM = 5,

@@ -69,8 +69,9 @@ def gather_kv(desc, k_pool, v_pool, k_scale, v_scale, bt_row, kv_begin, kv_end):
     """K[L,Hkv,Dk], V[L,Hkv,Dv] in float64 for tokens [kv_begin,kv_end) of one block-table row.
 
     Token t lives in physical page bt_row[t // ps], slot t % ps.
-      GQA:  K[t,h,d]  = k_pool[page, h, d // x, slot, d % x]
-            V[t,h,dv] = v_pool[page, h, slot // x, dv, slot % x]        (x = elements per 16 bytes)
+      GQA:  K[t,h,d]  = k_pool[page, h, slot // 4x, d // x, slot % 4x, d % x]
+            V[t,h,dv] = v_pool[page, h, u, dv, e]                       (x = elements per 16 bytes)
+                 with w = slot % 4x,  u = 4*(slot // 4x) + (w % 16) // 4,  e = 4*(w // 16) + w % 4
       MLA:  K[t,0,:]  = k_pool[page, slot, :],   V[t,0,:] = K[t,0,:Dv]
     """
     ps = desc.page_size
@@ -83,9 +84,12 @@ def gather_kv(desc, k_pool, v_pool, k_scale, v_scale, bt_row, kv_begin, kv_end):
         V = K[:, :, :desc.head_dim_v]
         return K, V
     x = k_pool.shape[-1]
-    K = decode_elems(k_pool[page, :, :, slot, :], desc.kv_dtype)          # [L,Hkv,Dk/x,x]
+    K = decode_elems(k_pool[page, :, slot // (4 * x), :, slot % (4 * x), :], desc.kv_dtype)   # [L,Hkv,Dk/x,x]
     K = K.reshape(L, desc.num_kv_heads, desc.head_dim_qk)
-    V = decode_elems(v_pool[page, :, slot // x, :, slot % x], desc.kv_dtype)  # [L,Hkv,Dv]
+    w = slot % (4 * x)
+    u = 4 * (slot // (4 * x)) + (w % 16) // 4
+    e = 4 * (w // 16) + w % 4
+    V = decode_elems(v_pool[page, :, u, :, e], desc.kv_dtype)              # [L,Hkv,Dv]
     V = V.reshape(L, desc.num_kv_heads, desc.head_dim_v)
     if desc.kv_dtype == "fp8":
         K = K * k_scale[page].astype(np.float64)[:, :, None]

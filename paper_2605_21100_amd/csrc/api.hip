@@ -7,8 +7,8 @@
 
 namespace nanocp {
 
-hipError_t launch_generic(const nanocp_attn_desc& d, const KParams& p, int num_chunks, hipStream_t st);
-hipError_t launch_gqa_mfma(int variant, const KParams& p, int num_chunks, hipStream_t st);
+hipError_t launch_generic(const nanocp_attn_desc& d, const KParams& p, int num_blocks, hipStream_t st);
+hipError_t launch_gqa_mfma(int variant, const KParams& p, int num_blocks, hipStream_t st);
 
 namespace {
 
@@ -45,40 +45,55 @@ __global__ __launch_bounds__(kThreads) void reduce_tiles_kernel(const Seg* segs,
 }
 
 // Phase 4: per (output, head) merge of the partials named by the CSR lists.
+// One thread per 4 consecutive output dims, so each thread has a single short chain of dependent loads.
 template <bool kBf16Out>
-__global__ __launch_bounds__(kThreads) void merge_kernel(const float* o_parts, const float* lse_parts,
-                                                         const int32_t* part_offsets, const int32_t* part_index,
-                                                         void* out, float* out_lse, int Hq, int Dv) {
+__global__ __launch_bounds__(kThreads) void merge_kernel(const float* __restrict__ o_parts,
+                                                         const float* __restrict__ lse_parts,
+                                                         const int32_t* __restrict__ part_offsets,
+                                                         const int32_t* __restrict__ part_index, void* __restrict__ out,
+                                                         float* __restrict__ out_lse, int Hq, int Dv) {
   const int r = blockIdx.x;
   const int b = part_offsets[r], e = part_offsets[r + 1];
-  for (int i = blockIdx.y * kThreads + threadIdx.x; i < Hq * Dv; i += gridDim.y * kThreads) {
-    const int a = i / Dv;
-    float top = -INFINITY;
+  const int q4 = Dv >> 2;  // float4 groups per head (Dv % 4 == 0 is checked by the host)
+  const int i4 = blockIdx.y * kThreads + threadIdx.x;
+  if (i4 >= Hq * q4) return;
+  const int a = i4 / q4;
+  const size_t row = (size_t)Hq * Dv;
+  float top = -INFINITY;
+  for (int k = b; k < e; ++k) {
+    const size_t pi = part_index ? part_index[k] : k;
+    top = fmaxf(top, lse_parts[pi * Hq + a]);
+  }
+  float tot = 0.f, lse = -INFINITY;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  if (top != -INFINITY) {
     for (int k = b; k < e; ++k) {
       const size_t pi = part_index ? part_index[k] : k;
-      top = fmaxf(top, lse_parts[pi * Hq + a]);
+      const float li = lse_parts[pi * Hq + a];
+      if (li == -INFINITY) continue;  // an empty partial's output is ignored whatever it holds
+      const float w = expf(li - top);
+      const float4 v = *(const float4*)(o_parts + pi * row + (size_t)i4 * 4);
+      tot += w;
+      acc[0] = fmaf(w, v.x, acc[0]);
+      acc[1] = fmaf(w, v.y, acc[1]);
+      acc[2] = fmaf(w, v.z, acc[2]);
+      acc[3] = fmaf(w, v.w, acc[3]);
     }
-    float tot = 0.f, acc = 0.f;
-    float res = 0.f, lse = -INFINITY;
-    if (top != -INFINITY) {
-      for (int k = b; k < e; ++k) {
-        const size_t pi = part_index ? part_index[k] : k;
-        const float li = lse_parts[pi * Hq + a];
-        if (li == -INFINITY) continue;  // an empty partial's output is ignored whatever it holds
-        const float w = expf(li - top);
-        tot += w;
-        acc = fmaf(w, o_parts[pi * (size_t)Hq * Dv + i], acc);
-      }
-      res = acc / tot;
-      lse = top + logf(tot);
-    }
-    const size_t oi = (size_t)r * Hq * Dv + i;
-    if (kBf16Out)
-      ((uint16_t*)out)[oi] = f32_to_bf16_rne(res);
-    else
-      ((float*)out)[oi] = res;
-    if (out_lse && i - a * Dv == 0) out_lse[(size_t)r * Hq + a] = lse;
+    const float inv = 1.f / tot;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[j] *= inv;
+    lse = top + logf(tot);
   }
+  const size_t oi = (size_t)r * row + (size_t)i4 * 4;
+  if (kBf16Out) {
+    uint2 pk;
+    pk.x = (uint32_t)f32_to_bf16_rne(acc[0]) | ((uint32_t)f32_to_bf16_rne(acc[1]) << 16);
+    pk.y = (uint32_t)f32_to_bf16_rne(acc[2]) | ((uint32_t)f32_to_bf16_rne(acc[3]) << 16);
+    *(uint2*)((uint16_t*)out + oi) = pk;
+  } else {
+    *(float4*)((float*)out + oi) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  }
+  if (out_lse && (i4 % q4) == 0) out_lse[(size_t)r * Hq + a] = lse;
 }
 
 nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_pool, const void* v_pool,
@@ -114,6 +129,8 @@ nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_
   p.ws_lse = (float*)((char*)workspace + o_bytes);
   p.tiles = plan->d_tiles;
   p.chunk_offsets = plan->d_chunk_offsets;
+  p.sync = plan->d_sync;
+  p.num_chunks = plan->num_chunks;
   p.tile_clock = tile_clock;
   p.Hq = d.num_q_heads;
   p.Hkv = d.num_kv_heads;
@@ -128,9 +145,9 @@ nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_
   if (plan->num_chunks > 0) {
     hipError_t e;
     if (plan->variant == kGeneric)
-      e = launch_generic(d, p, plan->num_chunks, st);
+      e = launch_generic(d, p, plan->launch_blocks, st);
     else
-      e = launch_gqa_mfma(plan->variant, p, plan->num_chunks, st);
+      e = launch_gqa_mfma(plan->variant, p, plan->launch_blocks, st);
     if (e != hipSuccess) return NANOCP_EHIP;
   }
   if (!plan->segs.empty()) {
@@ -173,8 +190,10 @@ nanocp_status nanocp_merge_partials(const nanocp_attn_desc* desc, const float* o
   if (num_out == 0) return NANOCP_OK;
   if (!o_parts || !lse_parts || !part_offsets || !out) return NANOCP_EINVAL;
   const int Hq = desc->num_q_heads, Dv = desc->head_dim_v;
-  const int per_out = (Hq * Dv + nanocp::kThreads - 1) / nanocp::kThreads;
-  dim3 grid((unsigned)num_out, (unsigned)(per_out < 8 ? per_out : 8));
+  if (Dv % 4) return NANOCP_ESHAPE;
+  if (((uintptr_t)o_parts | (uintptr_t)out) & 15) return NANOCP_EINVAL;
+  const int per_out = (Hq * (Dv / 4) + nanocp::kThreads - 1) / nanocp::kThreads;
+  dim3 grid((unsigned)num_out, (unsigned)per_out);
   hipStream_t st = (hipStream_t)stream;
   if (out_dtype == NANOCP_BF16)
     hipLaunchKernelGGL((nanocp::merge_kernel<true>), grid, dim3(nanocp::kThreads), 0, st, o_parts, lse_parts,

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kThreads) void generic_partial_kernel(KParams p) {
 
   const int t0 = p.chunk_offsets[blockIdx.x], t1 = p.chunk_offsets[blockIdx.x + 1];
   for (int ti = t0; ti < t1; ++ti) {
-    const nanocp_tile tile = p.tiles[ti];
+    const DevTile tile = p.tiles[ti];
     uint64_t clk0 = 0;
     if (p.tile_clock && tid == 0) clk0 = wall_clock64();
     const int h = tile.kv_head;
@@ -96,9 +96,10 @@ __global__ __launch_bounds__(kThreads) void generic_partial_kernel(KParams p) {
               const size_t base = ((size_t)page * ps + slot) * Dk;
               for (int d = 0; d < Dk; ++d) dot = fmaf(qg[d], ld_elem(kp, base + d), dot);
             } else {
-              const size_t base = ((size_t)page * Hkv + h) * (size_t)(Dk / x) * ps * x;
+              // K: token groups of 4x slots, [group][Dk/x][4x][x]
+              const size_t base = (((size_t)page * Hkv + h) * (ps / (4 * x)) + slot / (4 * x)) * (size_t)(Dk / x) * 4 * x * x;
               for (int c = 0; c < Dk / x; ++c) {
-                const size_t vb = base + ((size_t)c * ps + slot) * x;
+                const size_t vb = base + ((size_t)c * 4 * x + slot % (4 * x)) * x;
 #pragma unroll
                 for (int e = 0; e < x; ++e) dot = fmaf(qg[c * x + e], ld_elem(kp, vb + e), dot);
               }
@@ -138,8 +139,12 @@ __global__ __launch_bounds__(kThreads) void generic_partial_kernel(KParams p) {
               size_t idx;
               if (mla)
                 idx = ((size_t)page * ps + slot) * Dk + dv;
-              else
-                idx = ((((size_t)page * Hkv + h) * (ps / x) + slot / x) * Dv + dv) * x + (slot % x);
+              else {
+                // V vector/element of a slot: groups of 4x slots, slot 16b+4g+i -> vector g, element 4b+i
+                const int w = slot % (4 * x);
+                const int u = 4 * (slot / (4 * x)) + (w % 16) / 4, e = 4 * (w / 16) + (w % 4);
+                idx = ((((size_t)page * Hkv + h) * (ps / x) + u) * Dv + dv) * x + e;
+              }
               a = fmaf(sc[g][j], ld_elem(mla ? kp : vp, idx), a);
             }
             acc[i] = a;
@@ -173,8 +178,8 @@ __global__ __launch_bounds__(kThreads) void generic_partial_kernel(KParams p) {
 
 }  // namespace
 
-hipError_t launch_generic(const nanocp_attn_desc& d, const KParams& p, int num_chunks, hipStream_t st) {
-  dim3 grid(num_chunks), block(kThreads);
+hipError_t launch_generic(const nanocp_attn_desc& d, const KParams& p, int num_blocks, hipStream_t st) {
+  dim3 grid(num_blocks), block(kThreads);
   if (d.kv_dtype == NANOCP_F32)
     hipLaunchKernelGGL((generic_partial_kernel<float, float>), grid, block, 0, st, p);
   else if (d.kv_dtype == NANOCP_BF16)

@@ -7,17 +7,23 @@
 // its own running max / sum / accumulator; they are combined through LDS once per tile.
 //
 // Data path.  K and V go from HBM straight into MFMA operand registers: the page layouts
-// ([Dk/x][ps][x] for K, [ps/x][Dv][x] for V, x = elements per 16 bytes) make every 16-byte vector a
-// ready operand fragment, and 16 consecutive lanes read 64..256 contiguous bytes.
+// (token groups of 4x slots; [Dk/x][4x][x] for K, [4][Dv][x] for V, x = elements per 16 bytes) make every 16-byte vector a
+// ready operand fragment, and 16 consecutive lanes always read 256 contiguous bytes (whole cache
+// lines, each touched by exactly one load instruction, which is what lets the streaming hint pay).
 //   scores:  S^T[token, head] = K[token, :] . Q[head, :]        v_mfma_f32_16x16x32_bf16, A = K, B = Q^T
 //   output:  O^T[dim,  head] += V^T[dim, token] P^T[token, head]                       A = V^T, B = P^T
-// The C layout of the first product (lane = head + 16*g holds 4 token rows 4g..4g+3) is turned into
-// the B layout of the second (lane holds 8 consecutive k) by choosing which token each row of the
-// score MFMA stands for; no cross-lane data movement is needed.
+// The C layout of the first product gives lane group g (lanes 16g..16g+15) the token rows 4g..4g+3 of
+// every 16-token block b; the B operand of the second wants lane group g to hold 8 (or 16) values of
+// consecutive k.  The V page layout stores exactly those tokens {16b + 4g + i} together in vector g
+// (element 4b + i), so the probabilities are in operand order as they come out of the softmax and no
+// cross-lane data movement is needed.
 // P is split into two bf16 terms (hi + lo) so that the P*V product keeps ~16 bits of P.
 // fp8 K/V are widened to bf16 in registers (exact); the per-(page, head) scales are applied to the
 // scores (K) and to P (V) in fp32.
 #include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <type_traits>
 
 #include "plan.h"
 
@@ -38,12 +44,34 @@ constexpr int kPS = 64;   // page size
 constexpr int kWaves = kThreads / 64;
 constexpr int kOPad = kD + 4;  // LDS row stride (floats) of the combine buffer
 
+// Read-only metadata (work-list, block table, fp8 scales) is never written by this kernel; reading it
+// through the constant address space lets wave-uniform reads use the scalar unit (SGPR results, own
+// wait counter) instead of occupying vector-memory slots.
+template <typename T>
+using cptr = const __attribute__((address_space(4))) T*;
+template <typename T>
+__device__ inline cptr<T> as_const(const T* ptr) {
+  return (cptr<T>)(uintptr_t)ptr;
+}
+
 __device__ inline f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
+// 16-byte load of K/V; kNT adds the non-temporal hint (K/V are read exactly once)
+template <bool kNT>
 __device__ inline u32x4 ldg16(const void* base, uint32_t byte_off) {
-  return *(const u32x4*)((const char*)base + byte_off);
+  const u32x4* ptr = (const u32x4*)((const char*)base + byte_off);
+  return kNT ? __builtin_nontemporal_load(ptr) : *ptr;
+}
+
+// Partials that another workgroup will read inside the same launch travel with device-scope
+// (L2-coherent across XCDs) stores and loads, so no cache-wide write-back or invalidate is needed.
+__device__ inline void st_dev(float* ptr, float v) {
+  __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float ld_dev(const float* ptr) {
+  return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __device__ inline uint32_t pack_bf16(float a, float b) {
@@ -97,7 +125,7 @@ struct StepRegs {
   float ks, vs;  // fp8 scales of the step's page
 };
 
-template <bool kFp8>
+template <bool kFp8, bool kNT>
 __global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
   constexpr int kStep = kFp8 ? 64 : 32;            // tokens per step
   constexpr int kEl = kFp8 ? 1 : 2;                // bytes per kv element
@@ -107,27 +135,40 @@ __global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
 
   __shared__ float o_s[kWaves][kG][kOPad];
   __shared__ float m_s[kWaves][kG], l_s[kWaves][kG];
+  __shared__ int next_s, arrive_s;
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: step indices, pages and branches stay uniform
   const int r = lane & 15, g = lane >> 4;
   const int Hkv = p.Hkv;
   const float c_log2 = p.scale * 1.4426950408889634f;
 
   // per-lane byte offsets inside a (page, head) block; the step's slot offset is added per step
-  // K vector (c, t) at (c*ps + t)*16.   score block b, row r  <->  token  slot0 + tokmap(r) + 4b
-  const int tokmap = kFp8 ? (16 * (r >> 2) + (r & 3)) : (8 * (r >> 2) + (r & 3));
-  const uint32_t k_lane = (uint32_t)((g * kPS + tokmap) * 16);
-  // V vector (u, c) at (u*Dv + c)*16.   lane (r, g): token group slot0/x + g, dim 16j + r
+  // K of a step's token group: vector (c, t) at (c*kStep + t)*16, t = slot inside the group.  Score block b,
+  // row r  <->  slot 16b + r, so 16 lanes read 256 contiguous bytes and a step reads one contiguous 8 KB run
+  const uint32_t k_lane = (uint32_t)((g * kStep + r) * 16);
+  // V vector (u, c) at (u*Dv + c)*16.   lane (r, g): vector slot0/x + g of the step's token group, dim 16j + r
   const uint32_t v_lane = (uint32_t)((g * kD + r) * 16);
 
-  const int t0 = p.chunk_offsets[blockIdx.x], t1 = p.chunk_offsets[blockIdx.x + 1];
+  // Work queue: workgroup b starts with chunk b, then pulls the next unclaimed chunk.  The queue is
+  // ordered from large to small chunks, so differences in speed between workgroups even out at the end.
+  const cptr<int32_t> chunk_offsets = as_const(p.chunk_offsets);
+  const cptr<int32_t> tile_words = as_const((const int32_t*)p.tiles);
+  for (int chunk = blockIdx.x; chunk < p.num_chunks;) {
+  const int t0 = chunk_offsets[chunk], t1 = chunk_offsets[chunk + 1];
   for (int ti = t0; ti < t1; ++ti) {
-    const nanocp_tile tile = p.tiles[ti];
+    DevTile tile;
+    {
+      const cptr<int32_t> w = tile_words + (size_t)ti * (sizeof(DevTile) / 4);
+      tile.q_row = w[0], tile.bt_row = w[1], tile.kv_head = w[2], tile.shard = w[3];
+      tile.tok_begin = w[4], tile.tok_end = w[5], tile.dst = w[6], tile.seg = w[7];
+      tile.n_parts = w[8], tile.slot_begin = w[9];
+    }
     uint64_t clk0 = 0;
     if (p.tile_clock && tid == 0) clk0 = wall_clock64();
     const int h = tile.kv_head;
-    const int32_t* __restrict__ bt = p.block_table + (size_t)tile.bt_row * p.max_blocks;
+    const cptr<int32_t> bt = as_const(p.block_table + (size_t)tile.bt_row * p.max_blocks);
     const int tb = tile.tok_begin, te = tile.tok_end;
 
     // Q fragments (B operand): lane (g, n = r) holds Q[n][dims of k-step s]
@@ -149,40 +190,50 @@ __global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
     float m_run = -INFINITY;  // running max of scaled (log2-domain) scores of head r
     float l_run = 0.f;        // this lane's share of the running sum
 
-    const int u_end = (te + kStep - 1) / kStep;
-    int u = tb / kStep + wave;
+    // Steps are kStep-aligned in the row's token coordinates.  Steps that lie entirely inside [tb, te)
+    // ("full") run in the pipelined loop; the at most two ragged ones (shard begins / ends inside a step)
+    // are taken separately, with masking, by the wavefronts that get the fewest full steps.
+    const int u_first = tb / kStep, u_last = (te - 1) / kStep;
+    const bool head_ragged = (tb % kStep) != 0, tail_ragged = (te % kStep) != 0;
+    int fb = u_first + (head_ragged ? 1 : 0);  // full steps [fb, fe)
+    int fe = u_last + 1 - (tail_ragged ? 1 : 0);
+    int rag0 = head_ragged ? u_first : -1;     // ragged steps (or -1)
+    int rag1 = (tail_ragged && !(head_ragged && u_last == u_first)) ? u_last : -1;
+    if (fe < fb) fe = fb;
+    const int u_end = fe;
+    int u = fb + wave;
 
-    auto load_step = [&](StepRegs<kFp8>& sr, int uu) {
+    auto page_of = [&](int uu) { return uu <= u_last ? bt[(uu * kStep) / kPS] : 0; };
+    auto load_step = [&](StepRegs<kFp8>& sr, int uu, int page) {
       const int tok0 = uu * kStep;
-      const int page = bt[tok0 / kPS];
       const uint32_t slot0 = (uint32_t)(tok0 % kPS);
       const size_t ph = ((size_t)page * Hkv + h) * kPageHeadBytes;
       const char* kb = (const char*)p.k_pool + ph;
       const char* vb = (const char*)p.v_pool + ph;
       if (kFp8) {
-        sr.ks = p.k_scale[(size_t)page * Hkv + h];
-        sr.vs = p.v_scale[(size_t)page * Hkv + h];
+        sr.ks = as_const(p.k_scale)[(size_t)page * Hkv + h];
+        sr.vs = as_const(p.v_scale)[(size_t)page * Hkv + h];
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
           for (int q2 = 0; q2 < 2; ++q2)
-            sr.k[b * 2 + q2] = ldg16(kb, k_lane + (uint32_t)((4 * q2 * kPS + slot0 + 4 * b) * 16));
+            sr.k[b * 2 + q2] = ldg16<kNT>(kb, k_lane + (uint32_t)((4 * q2 * kStep + 16 * b) * 16));
 #pragma unroll
-        for (int j = 0; j < 8; ++j) sr.v[j] = ldg16(vb, v_lane + (uint32_t)(((slot0 / 16) * kD + 16 * j) * 16));
+        for (int j = 0; j < 8; ++j) sr.v[j] = ldg16<kNT>(vb, v_lane + (uint32_t)(((slot0 / 16) * kD + 16 * j) * 16));
       } else {
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int s = 0; s < 4; ++s)
-            sr.k[b * 4 + s] = ldg16(kb, k_lane + (uint32_t)((4 * s * kPS + slot0 + 4 * b) * 16));
+            sr.k[b * 4 + s] = ldg16<kNT>(kb, k_lane + (uint32_t)((slot0 * kD / 8 + 4 * s * kStep + 16 * b) * 16));
 #pragma unroll
-        for (int j = 0; j < 8; ++j) sr.v[j] = ldg16(vb, v_lane + (uint32_t)(((slot0 / 8) * kD + 16 * j) * 16));
+        for (int j = 0; j < 8; ++j) sr.v[j] = ldg16<kNT>(vb, v_lane + (uint32_t)(((slot0 / 8) * kD + 16 * j) * 16));
       }
     };
 
-    auto compute_step = [&](StepRegs<kFp8>& sr, int uu) {
+    auto compute_step = [&](StepRegs<kFp8>& sr, int uu, auto ragged_tag) {
+      constexpr bool ragged = decltype(ragged_tag)::value;
       const int tok0 = uu * kStep;
-      const bool ragged = tok0 < tb || tok0 + kStep > te;  // wavefront-uniform
       // ---- scores
       f32x4 S[kBlocks];
 #pragma unroll
@@ -200,7 +251,8 @@ __global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
           for (int s = 0; s < 4; ++s) S[b] = mfma16(__builtin_bit_cast(bf16x8, sr.k[b * 4 + s]), qf[s], S[b]);
         }
       }
-      // ---- online softmax in the log2 domain.  S[b][i] is token tok0 + x*g + 4b + i (x = tokens per V vector)
+      // ---- online softmax in the log2 domain.  S[b][i] is token tok0 + 16b + 4g + i, which the V layout
+      // stores as element 4b + i of the step's vector g: the scores are already in P*V operand order
       const float cs = kFp8 ? c_log2 * sr.ks : c_log2;
       float y[kNS];
       float mloc = -INFINITY;
@@ -210,7 +262,7 @@ __global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
         for (int i = 0; i < 4; ++i) {
           float v = S[b][i] * cs;
           if (ragged) {
-            const int tok = tok0 + (kFp8 ? 16 : 8) * g + 4 * b + i;
+            const int tok = tok0 + 16 * b + 4 * g + i;
             v = (tok >= tb && tok < te) ? v : -INFINITY;
           }
           y[b * 4 + i] = v;
@@ -240,14 +292,14 @@ __global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
       // ---- mask unused token slots of V (they may hold NaN patterns)
       if (ragged) {
         if (kFp8) {
-          // lane's V vector j: bytes e = 0..15 <-> tokens tok0 + 16g + e
+          // lane's V vector: byte 4w + e  <->  token tok0 + 16w + 4g + e
           u32x4 mk;
 #pragma unroll
           for (int w = 0; w < 4; ++w) {
             uint32_t mw = 0;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const int tok = tok0 + 16 * g + 4 * w + e;
+              const int tok = tok0 + 16 * w + 4 * g + e;
               if (tok >= tb && tok < te) mw |= 0xffu << (8 * e);
             }
             mk[w] = mw;
@@ -260,8 +312,8 @@ __global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
           for (int w = 0; w < 4; ++w) {
             uint32_t mw = 0;
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-              const int tok = tok0 + 8 * g + 2 * w + e;
+            for (int e = 0; e < 2; ++e) {  // element 2w + e = 4b + i  <->  token tok0 + 16b + 4g + i
+              const int tok = tok0 + 16 * (w >> 1) + 4 * g + 2 * (w & 1) + e;
               if (tok >= tb && tok < te) mw |= 0xffffu << (16 * e);
             }
             mk[w] = mw;
@@ -272,7 +324,7 @@ __global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
       }
       // ---- O^T += V^T P^T
       if (kFp8) {
-        bf16x8 hi0, lo0, hi1, lo1;  // tokens 16g+0..7 (score blocks 0,1) and 16g+8..15 (blocks 2,3)
+        bf16x8 hi0, lo0, hi1, lo1;  // vector elements 0..7 (score blocks 0,1) and 8..15 (blocks 2,3)
         split8(pr, hi0, lo0);
         split8(pr + 8, hi1, lo1);
 #pragma unroll
@@ -296,18 +348,39 @@ __global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
       }
     };
 
+    // software pipeline over the full steps: the loads of step n+1 are in flight while step n is
+    // computed, and the block-table entry of step n+2 is fetched one step ahead.  The steady state has
+    // no conditional loads, so the wait for the older buffer is a counted one, not a drain.
     StepRegs<kFp8> ra, rb;
-    if (u < u_end) load_step(ra, u);
-    while (u < u_end) {
-      int un = u + kWaves;
-      if (un < u_end) load_step(rb, un);
-      compute_step(ra, u);
-      u = un;
-      if (u >= u_end) break;
-      un = u + kWaves;
-      if (un < u_end) load_step(ra, un);
-      compute_step(rb, u);
-      u = un;
+    if (u < u_end) {
+      load_step(ra, u, page_of(u));
+      int pg_next = page_of(u + kWaves);
+      while (true) {
+        if (u + kWaves >= u_end) {
+          compute_step(ra, u, std::false_type{});
+          break;
+        }
+        load_step(rb, u + kWaves, pg_next);
+        pg_next = page_of(u + 2 * kWaves);
+        compute_step(ra, u, std::false_type{});
+        u += kWaves;
+        if (u + kWaves >= u_end) {
+          compute_step(rb, u, std::false_type{});
+          break;
+        }
+        load_step(ra, u + kWaves, pg_next);
+        pg_next = page_of(u + 2 * kWaves);
+        compute_step(rb, u, std::false_type{});
+        u += kWaves;
+      }
+    }
+    // ragged steps: the head by the last wavefront, the tail by the one before it
+    {
+      const int ru = wave == kWaves - 1 ? rag0 : (wave == kWaves - 2 ? rag1 : -1);
+      if (ru >= 0) {
+        load_step(ra, ru, page_of(ru));
+        compute_step(ra, ru, std::true_type{});
+      }
     }
 
     // ---- combine the 4 wavefronts' partials
@@ -348,18 +421,46 @@ __global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
           o[4 + e] = fmaf(fw, b[e], o[4 + e]);
         }
       }
-      float* dst_o;
-      float* dst_l;
-      if (tile.dst >= 0) {
-        dst_o = p.ws_o + (size_t)tile.dst * kG * kD;
-        dst_l = p.ws_lse + (size_t)tile.dst * kG;
+      const float lse_nat = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
+      if (tile.dst < 0) {
+        // the only tile of its (shard, head): final rows
+        float* dst_o = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG + n) * kD + d0;
+        *(f32x4*)dst_o = f32x4{o[0], o[1], o[2], o[3]};
+        *(f32x4*)(dst_o + 4) = f32x4{o[4], o[5], o[6], o[7]};
+        if ((tid & 15) == 0) p.out_lse[(size_t)tile.shard * p.Hq + (size_t)h * kG + n] = lse_nat;
       } else {
-        dst_o = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG) * kD;
-        dst_l = p.out_lse + (size_t)tile.shard * p.Hq + (size_t)h * kG;
+        // one of several tiles: publish the partial, and let the workgroup that delivers the last one
+        // LSE-combine them (same operator as the Phase 4 merge) into the shard's rows
+        float* dst_o = p.ws_o + ((size_t)tile.dst * kG + n) * kD + d0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st_dev(dst_o + e, o[e]);
+        if ((tid & 15) == 0) st_dev(p.ws_lse + (size_t)tile.dst * kG + n, lse_nat);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // own stores have completed (they write through)
+        __syncthreads();
+        if (tid == 0) arrive_s = atomicAdd(&p.sync[kSyncSegBase + tile.seg], 1);
+        __syncthreads();
+        if (arrive_s == tile.n_parts - 1) {
+          const float* wl = p.ws_lse + (size_t)tile.slot_begin * kG + n;
+          const float* wo = p.ws_o + ((size_t)tile.slot_begin * kG + n) * kD + d0;
+          float top = -INFINITY;
+          for (int k = 0; k < tile.n_parts; ++k) top = fmaxf(top, ld_dev(wl + (size_t)k * kG));
+          float tot = 0.f, r8[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) r8[e] = 0.f;
+          for (int k = 0; k < tile.n_parts; ++k) {
+            const float w = expf(ld_dev(wl + (size_t)k * kG) - top);
+            tot += w;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) r8[e] = fmaf(w, ld_dev(wo + (size_t)k * kG * kD + e), r8[e]);
+          }
+          const float rinv = 1.f / tot;
+          float* fo = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG + n) * kD + d0;
+          *(f32x4*)fo = f32x4{r8[0] * rinv, r8[1] * rinv, r8[2] * rinv, r8[3] * rinv};
+          *(f32x4*)(fo + 4) = f32x4{r8[4] * rinv, r8[5] * rinv, r8[6] * rinv, r8[7] * rinv};
+          if ((tid & 15) == 0) p.out_lse[(size_t)tile.shard * p.Hq + (size_t)h * kG + n] = top + logf(tot);
+          if (tid == 0) p.sync[kSyncSegBase + tile.seg] = 0;  // ready for the next launch
+        }
       }
-      *(f32x4*)(dst_o + n * kD + d0) = f32x4{o[0], o[1], o[2], o[3]};
-      *(f32x4*)(dst_o + n * kD + d0 + 4) = f32x4{o[4], o[5], o[6], o[7]};
-      if ((tid & 15) == 0) dst_l[n] = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
     }
     __syncthreads();
     if (p.tile_clock && tid == 0) {
@@ -367,18 +468,42 @@ __global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
       p.tile_clock[2 * (size_t)ti + 1] = wall_clock64();
     }
   }
+  if (tid == 0) next_s = (int)gridDim.x + atomicAdd(&p.sync[0], 1);
+  __syncthreads();
+  chunk = __builtin_amdgcn_readfirstlane(next_s);
+  __syncthreads();
+  }
+  // the last workgroup to leave re-arms the queue for the next launch
+  if (tid == 0) {
+    const int done = atomicAdd(&p.sync[1], 1);
+    if (done == (int)gridDim.x - 1) {
+      p.sync[0] = 0;
+      p.sync[1] = 0;
+    }
+  }
 }
 
 }  // namespace
 
-hipError_t launch_gqa_mfma(int variant, const KParams& p, int num_chunks, hipStream_t st) {
-  dim3 grid(num_chunks), block(kThreads);
-  if (variant == kGqaMfmaBf16)
-    hipLaunchKernelGGL((gqa_mfma_kernel<false>), grid, block, 0, st, p);
-  else if (variant == kGqaMfmaFp8)
-    hipLaunchKernelGGL((gqa_mfma_kernel<true>), grid, block, 0, st, p);
-  else
+hipError_t launch_gqa_mfma(int variant, const KParams& p, int num_blocks, hipStream_t st) {
+  dim3 grid(num_blocks), block(kThreads);
+  static const bool nt = [] {
+    const char* v = std::getenv("NANOCP_KV_NONTEMPORAL");
+    return !(v && v[0] == '0');
+  }();
+  if (variant == kGqaMfmaBf16) {
+    if (nt)
+      hipLaunchKernelGGL((gqa_mfma_kernel<false, true>), grid, block, 0, st, p);
+    else
+      hipLaunchKernelGGL((gqa_mfma_kernel<false, false>), grid, block, 0, st, p);
+  } else if (variant == kGqaMfmaFp8) {
+    if (nt)
+      hipLaunchKernelGGL((gqa_mfma_kernel<true, true>), grid, block, 0, st, p);
+    else
+      hipLaunchKernelGGL((gqa_mfma_kernel<true, false>), grid, block, 0, st, p);
+  } else {
     return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

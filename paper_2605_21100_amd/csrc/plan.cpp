@@ -8,6 +8,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <new>
 
 #include "plan.h"
@@ -30,7 +31,7 @@ nanocp_status check_desc(const nanocp_attn_desc& d) {
     if (d.num_kv_heads != 1 || d.head_dim_v > d.head_dim_qk) return NANOCP_ESHAPE;
     if (d.head_dim_qk % x) return NANOCP_ESHAPE;
   } else {
-    if (d.head_dim_qk % x || d.page_size % x) return NANOCP_ESHAPE;
+    if (d.head_dim_qk % x || d.page_size % (4 * x)) return NANOCP_ESHAPE;  // V is laid out in groups of 4x tokens
   }
   const bool combo = (d.q_dtype == NANOCP_F32 && d.kv_dtype == NANOCP_F32) ||
                      (d.q_dtype == NANOCP_BF16 && d.kv_dtype == NANOCP_BF16) ||
@@ -50,9 +51,14 @@ int pick_variant(const nanocp_attn_desc& d) {
   return kGeneric;
 }
 
-int workgroups_per_cu(int variant) {
-  (void)variant;
-  return 2;
+// Planner tuning knobs can be overridden from the environment (integers, clamped).
+int env_int(const char* name, int dflt, int lo, int hi) {
+  const char* v = std::getenv(name);
+  if (!v || !*v) return dflt;
+  char* end = nullptr;
+  const long x = std::strtol(v, &end, 10);
+  if (end == v) return dflt;
+  return (int)std::min<long>(hi, std::max<long>(lo, x));
 }
 
 }  // namespace
@@ -94,41 +100,60 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
     p->variant = pick_variant(*desc);
     const int Hkv = desc->num_kv_heads;
     const int G = desc->num_q_heads / Hkv;
-    const int c0 = kTileOverheadPages;
+    p->dynamic = p->variant != kGeneric;
+    const int c0 = env_int("NANOCP_PLAN_OVERHEAD_PAGES", 2, 0, 64);  // cost of a tile's Q load, combine, write-back
+    const int min_pages = env_int("NANOCP_PLAN_MIN_PAGES", 8, 1, 1 << 20);
+    const double static_frac = env_int("NANOCP_PLAN_STATIC_PCT", 80, 1, 100) / 100.0;
+    const int gss_k = env_int("NANOCP_PLAN_GSS_K", 2, 1, 64);
+    const int64_t M = std::max<int64_t>(1, (int64_t)num_cus * env_int("NANOCP_PLAN_WGS_PER_CU", 1, 1, 16));
 
-    // total cost in page units
-    int64_t units = 0;
+    // longest shards first: the big, statically sized chunks at the head of the queue then hold the long
+    // shards, and the small chunks at its tail are mostly whole short requests (no partials to reduce)
+    std::vector<int> order;
+    int64_t units = 0;  // total cost in page units
     for (int s = 0; s < num_shards; ++s) {
       const nanocp_shard& sh = shards[s];
       if (sh.kv_end == sh.kv_begin) continue;
+      order.push_back(s);
       const int64_t np = (sh.kv_end - 1) / ps - sh.kv_begin / ps + 1;
       units += (np + c0) * Hkv;
     }
-    const int64_t target_chunks = std::max<int64_t>(1, (int64_t)num_cus * workgroups_per_cu(p->variant));
-    int64_t cap;
-    const bool fixed = tile_tokens > 0;
-    if (fixed) {
-      cap = std::max<int64_t>(1, tile_tokens / ps) + c0;
-    } else {
-      cap = std::max<int64_t>((units + target_chunks - 1) / target_chunks, c0 + 4);
-    }
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+      return shards[a].kv_end - shards[a].kv_begin > shards[b].kv_end - shards[b].kv_begin;
+    });
 
-    for (int attempt = 0;; ++attempt) {
-      p->tiles.clear();
+    const bool fixed = tile_tokens > 0;
+    const int64_t cap_fixed = std::max<int64_t>(1, tile_tokens / ps) + c0;
+    const int64_t cap_static =
+        std::max<int64_t>((int64_t)(static_frac * (double)units / (double)M + 0.999), c0 + min_pages);
+    const int64_t whole_max = std::max<int64_t>(c0 + min_pages, cap_static / env_int("NANOCP_PLAN_WHOLE_DIV", 2, 1, 64));
+    int64_t consumed = 0;
+    auto open_cap = [&](int chunk_idx) -> int64_t {
+      if (fixed) return cap_fixed;
+      if (!p->dynamic) return std::max<int64_t>((units + M - 1) / M, c0 + min_pages);  // one chunk per workgroup
+      if (chunk_idx < M) return cap_static;
+      // guided self-scheduling over what is left: ever smaller chunks even out the finish times
+      return std::max<int64_t>(c0 + min_pages, (units - consumed) / (gss_k * M));
+    };
+
+    {
       int chunk = 0;
-      int64_t used = 0;
-      for (int s = 0; s < num_shards; ++s) {
+      int64_t used = 0, cap = open_cap(0);
+      for (int s : order) {
         const nanocp_shard& sh = shards[s];
-        if (sh.kv_end == sh.kv_begin) continue;
         const int pb = sh.kv_begin / ps, pe = (sh.kv_end - 1) / ps + 1;
         for (int h = 0; h < Hkv; ++h) {
           int pg = pb;
           while (pg < pe) {
-            if (used > 0 && cap - used < c0 + 1) {
+            // tail of the queue: a short (shard, head) is kept whole so that it needs no partials
+            const bool whole = !fixed && p->dynamic && chunk >= M && pg == pb && (pe - pb) + c0 <= whole_max;
+            const int64_t need = whole ? (pe - pb) + c0 : c0 + 1;
+            if (used > 0 && cap - used < need) {
               ++chunk;
               used = 0;
+              cap = open_cap(chunk);
             }
-            const int take = (int)std::min<int64_t>(pe - pg, cap - used - c0);
+            const int take = whole ? pe - pb : (int)std::min<int64_t>(pe - pg, cap - used - c0);
             nanocp_tile t;
             t.shard = s;
             t.kv_head = h;
@@ -140,14 +165,14 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
             t.chunk = chunk;
             p->tiles.push_back(t);
             used += c0 + take;
+            consumed += c0 + take;
             pg += take;
           }
         }
       }
       p->num_chunks = p->tiles.empty() ? 0 : chunk + 1;
-      if (fixed || p->num_chunks <= target_chunks || attempt > 64) break;
-      cap += std::max<int64_t>(1, cap / 64);
     }
+    p->launch_blocks = p->dynamic ? (int32_t)std::min<int64_t>(p->num_chunks, M) : p->num_chunks;
 
     // chunk offsets
     p->chunk_offsets.assign(p->num_chunks + 1, 0);
@@ -156,24 +181,28 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
 
     // partial slots and reduction segments: tiles of one (shard, head) are consecutive in the list
     p->num_slots = 0;
-    size_t i = 0;
-    int next_shard = 0;
-    auto add_empty = [&](int upto) {
-      for (; next_shard < upto; ++next_shard)
-        if (shards[next_shard].kv_end == shards[next_shard].kv_begin)
-          for (int h = 0; h < Hkv; ++h) p->segs.push_back(Seg{next_shard, h, 0, 0});
-    };
-    while (i < p->tiles.size()) {
+    p->num_multi_segs = 0;
+    p->dev_tiles.resize(p->tiles.size());
+    for (size_t i = 0; i < p->tiles.size();) {
       size_t j = i;
       while (j < p->tiles.size() && p->tiles[j].shard == p->tiles[i].shard && p->tiles[j].kv_head == p->tiles[i].kv_head) ++j;
-      add_empty(p->tiles[i].shard);
-      if (j - i > 1) {
-        p->segs.push_back(Seg{p->tiles[i].shard, p->tiles[i].kv_head, p->num_slots, (int32_t)(j - i)});
+      const int n = (int)(j - i);
+      const int slot_begin = p->num_slots;
+      if (n > 1) {
+        if (!p->dynamic) p->segs.push_back(Seg{p->tiles[i].shard, p->tiles[i].kv_head, slot_begin, n});
         for (size_t k = i; k < j; ++k) p->tiles[k].dst = p->num_slots++;
       }
+      for (size_t k = i; k < j; ++k) {
+        const nanocp_tile& t = p->tiles[k];
+        p->dev_tiles[k] = DevTile{t.q_row, t.bt_row, t.kv_head, t.shard, t.tok_begin, t.tok_end, t.dst,
+                                  n > 1 ? p->num_multi_segs : -1, n, slot_begin, 0, 0};
+      }
+      if (n > 1) p->num_multi_segs++;
       i = j;
     }
-    add_empty(num_shards);
+    for (int s = 0; s < num_shards; ++s)
+      if (shards[s].kv_end == shards[s].kv_begin)
+        for (int h = 0; h < Hkv; ++h) p->segs.push_back(Seg{s, h, 0, 0});
     // workspace: o partials [slots, G, Dv] then lse partials [slots, G], each 256-byte aligned
     const size_t o_bytes = ((size_t)p->num_slots * G * desc->head_dim_v * sizeof(float) + 255) & ~(size_t)255;
     const size_t l_bytes = ((size_t)p->num_slots * G * sizeof(float) + 255) & ~(size_t)255;
@@ -225,9 +254,14 @@ nanocp_status nanocp_plan_upload(nanocp_plan* plan, void* stream) {
     return NANOCP_OK;
   };
   nanocp_status s;
-  if ((s = up((void**)&plan->d_tiles, plan->tiles.data(), plan->tiles.size() * sizeof(nanocp_tile))) != NANOCP_OK) return s;
+  if ((s = up((void**)&plan->d_tiles, plan->dev_tiles.data(), plan->dev_tiles.size() * sizeof(DevTile))) != NANOCP_OK) return s;
   if ((s = up((void**)&plan->d_chunk_offsets, plan->chunk_offsets.data(), plan->chunk_offsets.size() * sizeof(int32_t))) != NANOCP_OK) return s;
   if ((s = up((void**)&plan->d_segs, plan->segs.data(), plan->segs.size() * sizeof(Seg))) != NANOCP_OK) return s;
+  {
+    const size_t sync_bytes = (size_t)(kSyncSegBase + plan->num_multi_segs) * sizeof(int32_t);
+    if (hipMalloc((void**)&plan->d_sync, sync_bytes) != hipSuccess) return NANOCP_ENOMEM;
+    if (hipMemsetAsync(plan->d_sync, 0, sync_bytes, st) != hipSuccess) return NANOCP_EHIP;
+  }
   // the host vectors must outlive the async copies: they live as long as the plan, and destroy synchronises
   plan->device = dev;
   return NANOCP_OK;
@@ -240,6 +274,7 @@ void nanocp_plan_destroy(nanocp_plan* plan) {
     if (plan->d_tiles) (void)hipFree(plan->d_tiles);
     if (plan->d_chunk_offsets) (void)hipFree(plan->d_chunk_offsets);
     if (plan->d_segs) (void)hipFree(plan->d_segs);
+    if (plan->d_sync) (void)hipFree(plan->d_sync);
   }
   delete plan;
 }

@@ -19,7 +19,21 @@ struct Seg {
 };
 
 constexpr int kThreads = 256;       // every kernel here runs 4 wavefronts per workgroup
-constexpr int kTileOverheadPages = 1;  // cost charged per tile for Q load, combine and write-back
+
+// Device-side tile record (the public nanocp_tile plus what the fused reduction needs).
+struct DevTile {
+  int32_t q_row, bt_row, kv_head, shard;
+  int32_t tok_begin, tok_end;
+  int32_t dst;         // partial slot, or -1 = write the final (shard, head) rows directly
+  int32_t seg;         // index of the (shard, head)'s arrival counter (valid if dst >= 0)
+  int32_t n_parts;     // tiles of this (shard, head)
+  int32_t slot_begin;  // first partial slot of this (shard, head)
+  int32_t pad0, pad1;
+};
+
+// sync words owned by the plan (zero between launches): [0] work-queue head, [1] finished workgroups,
+// [kSyncSegBase + i] arrivals at reduction segment i
+constexpr int kSyncSegBase = 2;
 
 // Arguments of the tile kernels (passed by value).
 struct KParams {
@@ -33,8 +47,10 @@ struct KParams {
   float* out_lse;
   float* ws_o;    // [num_slots, G, Dv]
   float* ws_lse;  // [num_slots, G]
-  const nanocp_tile* tiles;
+  const DevTile* tiles;
   const int32_t* chunk_offsets;
+  int32_t* sync;         // plan-owned counters (see kSyncSegBase)
+  int32_t num_chunks;
   uint64_t* tile_clock;  // may be null
   int32_t Hq, Hkv, G, Dk, Dv, ps, max_blocks, kind;
   float scale;
@@ -51,10 +67,15 @@ struct nanocp_plan {
   size_t workspace_bytes;
   std::vector<nanocp_tile> tiles;       // grouped by chunk, in execution order
   std::vector<int32_t> chunk_offsets;   // [num_chunks + 1]
-  std::vector<nanocp::Seg> segs;
+  std::vector<nanocp::DevTile> dev_tiles;
+  std::vector<nanocp::Seg> segs;        // segments the separate reduce kernel handles
+  int32_t num_multi_segs;               // (shard, head) pairs with more than one tile
+  int32_t launch_blocks;                // workgroups to launch
+  bool dynamic;                         // workgroups pull chunks from a queue and reduce partials themselves
   // device copy
   int device = -1;
-  nanocp_tile* d_tiles = nullptr;
+  nanocp::DevTile* d_tiles = nullptr;
   int32_t* d_chunk_offsets = nullptr;
   nanocp::Seg* d_segs = nullptr;
+  int32_t* d_sync = nullptr;
 };

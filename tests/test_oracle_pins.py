@@ -208,40 +208,44 @@ def test_generator_encoders_round_trip():
 
 
 # ---- 10. page layout: a packer written with explicit loops from the layout statement
-def _pack_loops(desc, K, V, bt_row, pages, begin):
-    """K[L,Hkv,Dk], V[L,Hkv,Dv] (float) -> pools in the documented layouts, token i stored at begin+i."""
-    x, ps = desc.vec, desc.page_size
+def _pack_loops(desc, x, K, V, bt_row, pages, begin):
+    """K[L,Hkv,Dk], V[L,Hkv,Dv] (float) -> pools in the documented layouts with x elements per vector
+    (the layout of 4-, 2- and 1-byte elements, here always holding floats), token i stored at begin+i."""
+    ps = desc.page_size
     if desc.kind == "mla":
         kp = np.zeros((pages, ps, desc.head_dim_qk), np.float32)
         for i in range(K.shape[0]):
             t = begin + i
             kp[bt_row[t // ps], t % ps, :] = K[i, 0]
         return kp, None
-    kp = np.zeros((pages, desc.num_kv_heads, desc.head_dim_qk // x, ps, x), np.float32)
+    kp = np.zeros((pages, desc.num_kv_heads, ps // (4 * x), desc.head_dim_qk // x, 4 * x, x), np.float32)
     vp = np.zeros((pages, desc.num_kv_heads, ps // x, desc.head_dim_v, x), np.float32)
     for i in range(K.shape[0]):
         t = begin + i
         p, slot = bt_row[t // ps], t % ps
         for h in range(desc.num_kv_heads):
             for d in range(desc.head_dim_qk):
-                kp[p, h, d // x, slot, d % x] = K[i, h, d]
+                kp[p, h, slot // (4 * x), d // x, slot % (4 * x), d % x] = K[i, h, d]
+            # V: groups of 4x slots; slot 16b + 4g + i of a group is element 4b + i of the group's vector g
+            grp, w = slot // (4 * x), slot % (4 * x)
+            b_, g_, i_ = w // 16, (w % 16) // 4, w % 4
             for c in range(desc.head_dim_v):
-                vp[p, h, slot // x, c, slot % x] = V[i, h, c]
+                vp[p, h, 4 * grp + g_, c, 4 * b_ + i_] = V[i, h, c]
     return kp, vp
 
 
-@pytest.mark.parametrize("kind", ["gqa", "mla"])
-def test_gather_matches_documented_layout(kind):
+@pytest.mark.parametrize("kind,x,ps", [("gqa", 4, 16), ("gqa", 8, 32), ("gqa", 16, 64), ("gqa", 8, 64), ("mla", 4, 8)])
+def test_gather_matches_documented_layout(kind, x, ps):
     rng = np.random.default_rng(10)
     if kind == "gqa":
-        desc = _desc("gqa", "f32", 4, 2, 8, 12, 8)
-        K, V = _rand(rng, 21, 2, 8).astype(np.float32), _rand(rng, 21, 2, 12).astype(np.float32)
+        desc = _desc("gqa", "f32", 4, 2, 16, 12, ps)
+        K, V = _rand(rng, 21, 2, 16).astype(np.float32), _rand(rng, 21, 2, 12).astype(np.float32)
     else:
         desc = _desc("mla", "f32", 4, 1, 12, 8, 8)
         K = _rand(rng, 21, 1, 12).astype(np.float32)
         V = K[:, :, :8]
     bt_row = np.array([5, 2, 7, 0], np.int32)
-    kp, vp = _pack_loops(desc, K, V, bt_row, 8, begin=3)
+    kp, vp = _pack_loops(desc, x, K, V, bt_row, 8, begin=3)
     Kg, Vg = oracle.gather_kv(desc, kp, vp, None, None, bt_row, 3, 24)
     np.testing.assert_array_equal(Kg, K.astype(np.float64))
     np.testing.assert_array_equal(Vg, V.astype(np.float64))

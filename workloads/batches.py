@@ -8,8 +8,11 @@ Both the float64 checker and the GPU library consume the very same raw buffers.
 
 Storage layouts (x = 16 bytes / sizeof(kv element): 4 for f32, 8 for bf16, 16 for fp8):
   q            [q_rows, Hq, Dk]                       f32, or bf16 bit patterns (uint16)
-  GQA k_pool   [pages, Hkv, Dk/x, ps, x]              16-byte vectors of x dims, token-major inside a dim chunk
-  GQA v_pool   [pages, Hkv, ps/x, Dv, x]              16-byte vectors of x tokens, dim-major inside a token chunk
+  GQA k_pool   [pages, Hkv, ps/4x, Dk/x, 4x, x]       token groups of 4x slots; inside a group, 16-byte vectors of
+                                                      x dims, token-major inside a dim chunk
+  GQA v_pool   [pages, Hkv, ps/x, Dv, x]              16-byte vectors of x tokens of one dim.  Inside every group of
+                                                      4x tokens, slot w = 16b + 4g + i (i < 4, g < 4) is element 4b + i
+                                                      of the group's vector g  (for f32, x = 4, that is plain order)
   MLA k_pool   [pages, ps, Dk]                        one latent row per token; V is its first Dv dims
   k_scale/v_scale [pages, Hkv] f32                    fp8 only
   block_table  [rows, max_blocks] int32               physical page ids, -1 past a row's last page
@@ -117,9 +120,15 @@ def _pool_shapes(desc, pages):
     x, ps = desc.vec, desc.page_size
     if desc.kind == "mla":
         return (pages, ps, desc.head_dim_qk), None
-    assert desc.head_dim_qk % x == 0 and ps % x == 0
-    return ((pages, desc.num_kv_heads, desc.head_dim_qk // x, ps, x),
+    assert desc.head_dim_qk % x == 0 and ps % (4 * x) == 0
+    return ((pages, desc.num_kv_heads, ps // (4 * x), desc.head_dim_qk // x, 4 * x, x),
             (pages, desc.num_kv_heads, ps // x, desc.head_dim_v, x))
+
+
+def v_slot(slot, x):
+    """(vector index, element) of a token slot inside a page of the V layout."""
+    grp, w = divmod(slot, 4 * x)
+    return grp * 4 + (w % 16) // 4, 4 * (w // 16) + w % 4
 
 
 def _draw_f32(rng, shape):
@@ -140,9 +149,10 @@ def _poison_slots(desc, k, v, page, lo, hi):
     if desc.kind == "mla":
         k[page, lo:hi, :] = nan
         return
-    k[page, :, :, lo:hi, :] = nan
     for t in range(lo, hi):
-        v[page, :, t // x, :, t % x] = nan
+        k[page, :, t // (4 * x), :, t % (4 * x), :] = nan
+        u, e = v_slot(t, x)
+        v[page, :, u, :, e] = nan
 
 
 def _encode_pool(desc, raw):
