@@ -146,24 +146,34 @@ def main():
 
     extra = {}
     if not args.no_straggle:
-        clk = torch.zeros((max(db.plan.num_tiles, 1), 2), dtype=torch.int64, device="cuda")
+        # per tile: device clock at start / end and the workgroup that ran it (instrumented entry point)
+        clk = torch.zeros((max(db.plan.num_tiles, 1), 3), dtype=torch.int64, device="cuda")
         for rep in range(3):
             nanocp.nanocp_decode_attn_partial(db.plan, db.q, *[pools[rep & 1][j] for j in range(4)], db.block_table,
                                               local_o, local_lse, db.workspace, tile_clock=clk)
         torch.cuda.synchronize()
         c = clk.cpu().numpy().astype(np.int64)
         tiles = db.plan.tiles()
-        per_chunk_start = np.full(db.plan.num_chunks, np.iinfo(np.int64).max)
-        per_chunk_end = np.zeros(db.plan.num_chunks, np.int64)
-        np.minimum.at(per_chunk_start, tiles["chunk"], c[:, 0])
-        np.maximum.at(per_chunk_end, tiles["chunk"], c[:, 1])
         if args.dump_tiles:
             np.savez(args.dump_tiles, tiles=tiles, clock=c)
-        chunk_t = (per_chunk_end - per_chunk_start).astype(np.float64) / 100.0       # 100 MHz clock -> microseconds
-        span = (per_chunk_end.max() - per_chunk_start.min()) / 100.0
-        extra = {"chunks": int(db.plan.num_chunks), "tiles": int(db.plan.num_tiles),
-                 "chunk_time_us_mean": float(chunk_t.mean()), "chunk_time_us_max": float(chunk_t.max()),
-                 "straggle_max_over_mean": float(chunk_t.max() / chunk_t.mean()), "kernel_span_us": float(span)}
+        t0 = c[:, 0].min()
+        wg = c[:, 2]
+        n_wg = int(wg.max()) + 1
+        finish = np.zeros(n_wg)
+        np.maximum.at(finish, wg, (c[:, 1] - t0) / 100.0)            # 100 MHz clock -> microseconds
+        # the first n_wg chunks of the queue have equal cost by construction: their run times are the
+        # "tile times" whose spread says how much one piece of the work-list can straggle
+        nch = db.plan.num_chunks
+        c_start = np.full(nch, np.iinfo(np.int64).max)
+        c_end = np.zeros(nch, np.int64)
+        np.minimum.at(c_start, tiles["chunk"], c[:, 0])
+        np.maximum.at(c_end, tiles["chunk"], c[:, 1])
+        head = ((c_end - c_start) / 100.0)[:min(n_wg, nch)]
+        extra = {"chunks": int(nch), "tiles": int(db.plan.num_tiles), "workgroups": n_wg,
+                 "wg_finish_us_mean": float(finish.mean()), "wg_finish_us_max": float(finish.max()),
+                 "straggle_wg_finish_max_over_mean": float(finish.max() / finish.mean()),
+                 "equal_chunk_us_mean": float(head.mean()), "equal_chunk_us_max": float(head.max()),
+                 "straggle_equal_chunk_max_over_mean": float(head.max() / head.mean())}
 
     result = {
         "metric": METRIC, "value": kv_bytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1,

@@ -95,7 +95,7 @@ typedef struct {
   int32_t tok_end;
   int32_t dst;     /* >= 0: partial slot in the workspace, reduced later; -1: the (shard, head) has a single tile
                       that writes out_o / out_lse directly */
-  int32_t chunk;   /* workgroup that executes the tile */
+  int32_t chunk;   /* work-queue entry the tile belongs to */
 } nanocp_tile;
 
 typedef struct nanocp_plan nanocp_plan; /* opaque, library-owned */
@@ -103,11 +103,13 @@ typedef struct nanocp_plan nanocp_plan; /* opaque, library-owned */
 /*
  * nanocp_plan_create -- build the split-KV tile work-list for one batch composition (HOST only).
  * The one-GPU analogue of the paper's balance objective (Dual-balanced Scheduling, WaterFill:
- * minimise the peak load): the flattened page list of all (shard, kv head) pairs is cut into
- * `num_chunks` spans of near-equal cost, so a very long shard is spread over many workgroups
- * while short requests are packed several to a workgroup.  Cuts fall on page boundaries.
+ * minimise the peak load): the page list of all (shard, kv head) pairs, longest shard first, is cut
+ * into chunks that workgroups pull from a queue: first one big chunk of equal cost per workgroup
+ * (~85 % of the work), then ever smaller ones that even out the finish times.  A very long shard is
+ * thereby spread over many workgroups while short requests are packed several to a chunk.  Cuts fall
+ * on page boundaries.
  *   shards            HOST, [num_shards]
- *   tile_tokens       0 = automatic (cost spread evenly over the GPU); > 0 caps a chunk at this many tokens
+ *   tile_tokens       0 = automatic (as above); > 0: every chunk holds at most this many tokens
  *   num_cus           compute units to plan for; 0 = query the current HIP device
  *   out               receives the plan; release with nanocp_plan_destroy
  * Errors: EINVAL, ESHAPE, EBOUNDS, EUNSUPPORTED, ENOMEM; EHIP only if num_cus == 0 and no device.
@@ -116,8 +118,9 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
                                  int32_t num_q_rows, int32_t num_bt_rows, int32_t max_blocks_per_row,
                                  int32_t tile_tokens, int32_t num_cus, nanocp_plan** out);
 
-/* Sizes the caller needs: number of tiles, number of chunks (= workgroups launched) and the
- * bytes of DEVICE workspace nanocp_decode_attn_partial requires (may be 0). Any out pointer may be NULL. */
+/* Sizes the caller needs: number of tiles, number of chunks (entries of the work queue; at most
+ * 1 workgroup per compute unit is launched and pulls them in order) and the bytes of DEVICE workspace
+ * nanocp_decode_attn_partial requires (may be 0). Any out pointer may be NULL. */
 nanocp_status nanocp_plan_query(const nanocp_plan* plan, int32_t* num_tiles, int32_t* num_chunks,
                                 size_t* workspace_bytes);
 
@@ -139,7 +142,9 @@ void nanocp_plan_destroy(nanocp_plan* plan);
  *   out_o, out_lse                                     DEVICE, written for every shard
  *   workspace                                          DEVICE scratch of at least the queried size
  *                                                      (16-byte aligned; contents need not be preserved)
- * Two launches on `stream`: the tile kernel, then the per-(shard, head) reduction of tile partials.
+ * One launch on `stream` for the MFMA variants (the workgroup that delivers the last tile of a (shard, head)
+ * also reduces its tile partials); the generic variant adds a small reduction launch.  A plan must not be
+ * run concurrently on two streams: launches share the plan's work-queue counters.
  * Errors: EINVAL (null), ESTATE (plan not uploaded), EBOUNDS (workspace too small), EHIP.
  */
 nanocp_status nanocp_decode_attn_partial(const nanocp_plan* plan, const void* q, const void* k_pool,
@@ -147,8 +152,9 @@ nanocp_status nanocp_decode_attn_partial(const nanocp_plan* plan, const void* q,
                                          const int32_t* block_table, float* out_o, float* out_lse,
                                          void* workspace, size_t workspace_bytes, void* stream);
 
-/* Same, and additionally records per tile the device wall clock (100 MHz ticks) at its start and end into
- * tile_clock[num_tiles][2] (DEVICE, uint64) -- used to report how much the slowest tile straggles. */
+/* Same, and additionally records per tile {device wall clock (100 MHz ticks) at its start, at its end, index of
+ * the workgroup that ran it} into tile_clock[num_tiles][3] (DEVICE, uint64) -- used to report how much the
+ * slowest workgroup straggles behind the mean. */
 nanocp_status nanocp_decode_attn_partial_timed(const nanocp_plan* plan, const void* q, const void* k_pool,
                                                const void* v_pool, const float* k_scale, const float* v_scale,
                                                const int32_t* block_table, float* out_o, float* out_lse,

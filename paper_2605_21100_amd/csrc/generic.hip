@@ -170,8 +170,9 @@ __global__ __launch_bounds__(kThreads) void generic_partial_kernel(KParams p) {
       if (tid < GH) dst_l[tid] = m_s[tid] + logf(l_s[tid]);
     }
     if (p.tile_clock && tid == 0) {
-      p.tile_clock[2 * (size_t)ti] = clk0;
-      p.tile_clock[2 * (size_t)ti + 1] = wall_clock64();
+      p.tile_clock[3 * (size_t)ti] = clk0;
+      p.tile_clock[3 * (size_t)ti + 1] = wall_clock64();
+      p.tile_clock[3 * (size_t)ti + 2] = blockIdx.x;
     }
   }
 }

@@ -126,7 +126,7 @@ struct StepRegs {
 };
 
 template <bool kFp8, bool kNT>
-__global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
+__global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
   constexpr int kStep = kFp8 ? 64 : 32;            // tokens per step
   constexpr int kEl = kFp8 ? 1 : 2;                // bytes per kv element
   constexpr int kBlocks = kStep / 16;              // score MFMA blocks per step
@@ -464,8 +464,9 @@ __global__ __launch_bounds__(kThreads, 2) void gqa_mfma_kernel(KParams p) {
     }
     __syncthreads();
     if (p.tile_clock && tid == 0) {
-      p.tile_clock[2 * (size_t)ti] = clk0;
-      p.tile_clock[2 * (size_t)ti + 1] = wall_clock64();
+      p.tile_clock[3 * (size_t)ti] = clk0;
+      p.tile_clock[3 * (size_t)ti + 1] = wall_clock64();
+      p.tile_clock[3 * (size_t)ti + 2] = blockIdx.x;
     }
   }
   if (tid == 0) next_s = (int)gridDim.x + atomicAdd(&p.sync[0], 1);

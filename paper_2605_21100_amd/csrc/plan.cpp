@@ -103,7 +103,7 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
     p->dynamic = p->variant != kGeneric;
     const int c0 = env_int("NANOCP_PLAN_OVERHEAD_PAGES", 2, 0, 64);  // cost of a tile's Q load, combine, write-back
     const int min_pages = env_int("NANOCP_PLAN_MIN_PAGES", 8, 1, 1 << 20);
-    const double static_frac = env_int("NANOCP_PLAN_STATIC_PCT", 80, 1, 100) / 100.0;
+    const double static_frac = env_int("NANOCP_PLAN_STATIC_PCT", 85, 1, 100) / 100.0;
     const int gss_k = env_int("NANOCP_PLAN_GSS_K", 2, 1, 64);
     const int64_t M = std::max<int64_t>(1, (int64_t)num_cus * env_int("NANOCP_PLAN_WGS_PER_CU", 1, 1, 16));
 
@@ -174,11 +174,6 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
     }
     p->launch_blocks = p->dynamic ? (int32_t)std::min<int64_t>(p->num_chunks, M) : p->num_chunks;
 
-    // chunk offsets
-    p->chunk_offsets.assign(p->num_chunks + 1, 0);
-    for (const nanocp_tile& t : p->tiles) p->chunk_offsets[t.chunk + 1]++;
-    for (int c = 0; c < p->num_chunks; ++c) p->chunk_offsets[c + 1] += p->chunk_offsets[c];
-
     // partial slots and reduction segments: tiles of one (shard, head) are consecutive in the list
     p->num_slots = 0;
     p->num_multi_segs = 0;
@@ -203,6 +198,34 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
     for (int s = 0; s < num_shards; ++s)
       if (shards[s].kv_end == shards[s].kv_begin)
         for (int h = 0; h < Hkv; ++h) p->segs.push_back(Seg{s, h, 0, 0});
+
+    // Queue order: the statically sized chunks first, then the rest by decreasing cost (longest
+    // processing time first), so that the very last chunks taken are the smallest ones.
+    if (p->dynamic && !fixed && p->num_chunks > M) {
+      std::vector<int64_t> cost(p->num_chunks, 0);
+      for (const nanocp_tile& t : p->tiles) cost[t.chunk] += (t.tok_end - 1) / ps - t.tok_begin / ps + 1 + c0;
+      std::vector<int> perm(p->num_chunks);
+      for (int c = 0; c < p->num_chunks; ++c) perm[c] = c;
+      std::stable_sort(perm.begin() + M, perm.end(), [&](int a, int b) { return cost[a] > cost[b]; });
+      std::vector<int> new_id(p->num_chunks);
+      for (int c = 0; c < p->num_chunks; ++c) new_id[perm[c]] = c;
+      std::vector<size_t> idx(p->tiles.size());
+      for (size_t i = 0; i < idx.size(); ++i) idx[i] = i;
+      std::stable_sort(idx.begin(), idx.end(),
+                       [&](size_t a, size_t b) { return new_id[p->tiles[a].chunk] < new_id[p->tiles[b].chunk]; });
+      std::vector<nanocp_tile> nt(p->tiles.size());
+      std::vector<DevTile> nd(p->tiles.size());
+      for (size_t i = 0; i < idx.size(); ++i) {
+        nt[i] = p->tiles[idx[i]];
+        nt[i].chunk = new_id[nt[i].chunk];
+        nd[i] = p->dev_tiles[idx[i]];
+      }
+      p->tiles.swap(nt);
+      p->dev_tiles.swap(nd);
+    }
+    p->chunk_offsets.assign(p->num_chunks + 1, 0);
+    for (const nanocp_tile& t : p->tiles) p->chunk_offsets[t.chunk + 1]++;
+    for (int c = 0; c < p->num_chunks; ++c) p->chunk_offsets[c + 1] += p->chunk_offsets[c];
     // workspace: o partials [slots, G, Dv] then lse partials [slots, G], each 256-byte aligned
     const size_t o_bytes = ((size_t)p->num_slots * G * desc->head_dim_v * sizeof(float) + 255) & ~(size_t)255;
     const size_t l_bytes = ((size_t)p->num_slots * G * sizeof(float) + 255) & ~(size_t)255;
