@@ -59,54 +59,67 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float* __restrict
   if (i4 >= Hq * q4) return;
   const int a = i4 / q4;
   const size_t row = (size_t)Hq * Dv;
-  // One pass with a running maximum, 8 parts at a time: the index loads of a batch are issued together,
-  // then its LSE and output loads, so a request with d <= 8 partials costs two memory round trips.
   float top = -INFINITY, tot = 0.f;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int k0 = b; k0 < e; k0 += 8) {
-    size_t pi[8];
-    float li[8];
-    float4 v[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int k = min(k0 + j, e - 1);
-      pi[j] = part_index ? (size_t)part_index[k] : (size_t)k;
+  if (e - b == 1) {
+    // a request held by one instance (the common case): its partial is the final output
+    const size_t pi = part_index ? (size_t)part_index[b] : (size_t)b;
+    const float li = lse_parts[pi * Hq + a];
+    const float4 v = *(const float4*)(o_parts + pi * row + (size_t)i4 * 4);
+    if (li != -INFINITY) {
+      top = li, tot = 1.f;
+      acc[0] = v.x, acc[1] = v.y, acc[2] = v.z, acc[3] = v.w;
     }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      li[j] = lse_parts[pi[j] * Hq + a];
-      v[j] = *(const float4*)(o_parts + pi[j] * row + (size_t)i4 * 4);
-    }
-    float bm = -INFINITY;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      if (k0 + j >= e) li[j] = -INFINITY;  // padding of the last batch
-      bm = fmaxf(bm, li[j]);
-    }
-    const float nt = fmaxf(top, bm);
-    if (nt != -INFINITY) {
-      const float sc = expf(top - nt);  // top = -inf on the first live batch: exp(-inf) = 0
-      tot *= sc;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) acc[c] *= sc;
+  } else {
+    // One pass with a running maximum, 8 parts at a time: the index loads of a batch are issued together,
+    // then its LSE and output loads, so a request with d <= 8 partials costs two memory round trips.
+    for (int k0 = b; k0 < e; k0 += 8) {
+      size_t pi[8];
+      float li[8];
+      float4 v[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const bool live = li[j] != -INFINITY;  // an empty partial's output is ignored whatever it holds
-        const float w = live ? expf(li[j] - nt) : 0.f;
-        tot += w;
-        acc[0] = fmaf(w, live ? v[j].x : 0.f, acc[0]);
-        acc[1] = fmaf(w, live ? v[j].y : 0.f, acc[1]);
-        acc[2] = fmaf(w, live ? v[j].z : 0.f, acc[2]);
-        acc[3] = fmaf(w, live ? v[j].w : 0.f, acc[3]);
+        const int k = min(k0 + j, e - 1);
+        pi[j] = part_index ? (size_t)part_index[k] : (size_t)k;
       }
-      top = nt;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        li[j] = lse_parts[pi[j] * Hq + a];
+        v[j] = *(const float4*)(o_parts + pi[j] * row + (size_t)i4 * 4);
+      }
+      float bm = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (k0 + j >= e) li[j] = -INFINITY;  // padding of the last batch
+        bm = fmaxf(bm, li[j]);
+      }
+      const float nt = fmaxf(top, bm);
+      if (nt != -INFINITY) {
+        const float sc = expf(top - nt);  // top = -inf on the first live batch: exp(-inf) = 0
+        tot *= sc;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] *= sc;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const bool live = li[j] != -INFINITY;  // an empty partial's output is ignored whatever it holds
+          const float w = live ? expf(li[j] - nt) : 0.f;
+          tot += w;
+          acc[0] = fmaf(w, live ? v[j].x : 0.f, acc[0]);
+          acc[1] = fmaf(w, live ? v[j].y : 0.f, acc[1]);
+          acc[2] = fmaf(w, live ? v[j].z : 0.f, acc[2]);
+          acc[3] = fmaf(w, live ? v[j].w : 0.f, acc[3]);
+        }
+        top = nt;
+      }
     }
   }
   float lse = -INFINITY;
   if (top != -INFINITY) {
-    const float inv = 1.f / tot;
+    if (tot != 1.f) {
+      const float inv = 1.f / tot;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[j] *= inv;
+      for (int j = 0; j < 4; ++j) acc[j] *= inv;
+    }
     lse = top + logf(tot);
   }
   const size_t oi = (size_t)r * row + (size_t)i4 * 4;

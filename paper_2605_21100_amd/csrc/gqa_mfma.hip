@@ -79,11 +79,10 @@ __device__ inline uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
-// two OCP E4M3 bytes (low or high half of w) -> two bf16, exact
+// two OCP E4M3 bytes (low or high half of w) -> two bf16, exact: v_cvt_scalef32_pk_bf16_fp8 with scale 1
 template <bool kHi>
 __device__ inline uint32_t fp8x2_to_bf16x2(uint32_t w) {
-  f32x2 f = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, kHi);
-  return pack_bf16(f.x, f.y);
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, kHi));
 }
 
 // 8 fp8 bytes (two dwords) -> 8 bf16
@@ -393,8 +392,8 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
     for (int j = 0; j < 8; ++j) *(f32x4*)&o_s[wave][r][16 * j + 4 * g] = acc[j];  // rows 4g+i of block j = dims 16j+4g+i
     __syncthreads();
     {
-      // thread <-> (head n, 8 consecutive dims)
-      const int n = tid >> 4, d0 = (tid & 15) * 8;
+      // thread <-> (head n, 8 dims)
+      const int n = tid >> 4, c16 = tid & 15;
       float mw[kWaves], M = -INFINITY;
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) {
@@ -408,40 +407,48 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
         L += f[w] * l_s[w][n];
       }
       const float inv = 1.f / L;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) f[w] *= inv;
+      const float lse_nat = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
       float o[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) o[e] = 0.f;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
-        const f32x4 a = *(const f32x4*)&o_s[w][n][d0], b = *(const f32x4*)&o_s[w][n][d0 + 4];
-        const float fw = f[w] * inv;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          o[e] = fmaf(fw, a[e], o[e]);
-          o[4 + e] = fmaf(fw, b[e], o[4 + e]);
-        }
-      }
-      const float lse_nat = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
       if (tile.dst < 0) {
-        // the only tile of its (shard, head): final rows
+        // the only tile of its (shard, head): final rows; the thread owns 8 consecutive dims (two 16-byte stores)
+        const int d0 = c16 * 8;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+          const f32x4 a = *(const f32x4*)&o_s[w][n][d0], b = *(const f32x4*)&o_s[w][n][d0 + 4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            o[e] = fmaf(f[w], a[e], o[e]);
+            o[4 + e] = fmaf(f[w], b[e], o[4 + e]);
+          }
+        }
         float* dst_o = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG + n) * kD + d0;
         *(f32x4*)dst_o = f32x4{o[0], o[1], o[2], o[3]};
         *(f32x4*)(dst_o + 4) = f32x4{o[4], o[5], o[6], o[7]};
-        if ((tid & 15) == 0) p.out_lse[(size_t)tile.shard * p.Hq + (size_t)h * kG + n] = lse_nat;
+        if (c16 == 0) p.out_lse[(size_t)tile.shard * p.Hq + (size_t)h * kG + n] = lse_nat;
       } else {
         // one of several tiles: publish the partial, and let the workgroup that delivers the last one
-        // LSE-combine them (same operator as the Phase 4 merge) into the shard's rows
-        float* dst_o = p.ws_o + ((size_t)tile.dst * kG + n) * kD + d0;
+        // LSE-combine them (same operator as the Phase 4 merge) into the shard's rows.  Here the thread owns
+        // dims c16 + 16e, so that each of the 4-byte device-scope stores / loads of 16 neighbouring lanes
+        // covers one whole 64-byte sector.
 #pragma unroll
-        for (int e = 0; e < 8; ++e) st_dev(dst_o + e, o[e]);
-        if ((tid & 15) == 0) st_dev(p.ws_lse + (size_t)tile.dst * kG + n, lse_nat);
+        for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = fmaf(f[w], o_s[w][n][c16 + 16 * e], o[e]);
+        float* dst_o = p.ws_o + ((size_t)tile.dst * kG + n) * kD + c16;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st_dev(dst_o + 16 * e, o[e]);
+        if (c16 == 0) st_dev(p.ws_lse + (size_t)tile.dst * kG + n, lse_nat);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // own stores have completed (they write through)
         __syncthreads();
         if (tid == 0) arrive_s = atomicAdd(&p.sync[kSyncSegBase + tile.seg], 1);
         __syncthreads();
         if (arrive_s == tile.n_parts - 1) {
           const float* wl = p.ws_lse + (size_t)tile.slot_begin * kG + n;
-          const float* wo = p.ws_o + ((size_t)tile.slot_begin * kG + n) * kD + d0;
+          const float* wo = p.ws_o + ((size_t)tile.slot_begin * kG + n) * kD + c16;
           float top = -INFINITY;
           for (int k = 0; k < tile.n_parts; ++k) top = fmaxf(top, ld_dev(wl + (size_t)k * kG));
           float tot = 0.f, r8[8];
@@ -451,13 +458,13 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
             const float w = expf(ld_dev(wl + (size_t)k * kG) - top);
             tot += w;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) r8[e] = fmaf(w, ld_dev(wo + (size_t)k * kG * kD + e), r8[e]);
+            for (int e = 0; e < 8; ++e) r8[e] = fmaf(w, ld_dev(wo + (size_t)k * kG * kD + 16 * e), r8[e]);
           }
           const float rinv = 1.f / tot;
-          float* fo = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG + n) * kD + d0;
-          *(f32x4*)fo = f32x4{r8[0] * rinv, r8[1] * rinv, r8[2] * rinv, r8[3] * rinv};
-          *(f32x4*)(fo + 4) = f32x4{r8[4] * rinv, r8[5] * rinv, r8[6] * rinv, r8[7] * rinv};
-          if ((tid & 15) == 0) p.out_lse[(size_t)tile.shard * p.Hq + (size_t)h * kG + n] = top + logf(tot);
+          float* fo = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG + n) * kD + c16;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) fo[16 * e] = r8[e] * rinv;
+          if (c16 == 0) p.out_lse[(size_t)tile.shard * p.Hq + (size_t)h * kG + n] = top + logf(tot);
           if (tid == 0) p.sync[kSyncSegBase + tile.seg] = 0;  // ready for the next launch
         }
       }
