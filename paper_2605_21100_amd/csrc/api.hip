@@ -9,6 +9,7 @@ namespace nanocp {
 
 hipError_t launch_generic(const nanocp_attn_desc& d, const KParams& p, int num_blocks, hipStream_t st);
 hipError_t launch_gqa_mfma(int variant, const KParams& p, int num_blocks, hipStream_t st);
+hipError_t launch_mla_mfma(const KParams& p, int num_blocks, hipStream_t st);
 
 namespace {
 
@@ -20,28 +21,58 @@ __device__ inline uint16_t f32_to_bf16_rne(float f) {
 }
 
 // LSE-combine of the tile partials of one (shard, kv head): the same operator as the Phase 4 merge,
-// applied inside the instance.  One workgroup per segment; thread <-> (head, dim) pairs.
-__global__ __launch_bounds__(kThreads) void reduce_tiles_kernel(const Seg* segs, const float* ws_o, const float* ws_lse,
-                                                                float* out_o, float* out_lse, int Hq, int G, int Dv) {
+// applied inside the instance (used by the variants that do not reduce inside the tile kernel, and to
+// fill empty shards).  One thread per 4 output dims; parts are taken 8 at a time with a running maximum.
+__global__ __launch_bounds__(kThreads) void reduce_tiles_kernel(const Seg* __restrict__ segs,
+                                                                const float* __restrict__ ws_o,
+                                                                const float* __restrict__ ws_lse,
+                                                                float* __restrict__ out_o, float* __restrict__ out_lse,
+                                                                int Hq, int G, int Dv) {
   const Seg sg = segs[blockIdx.x];
-  const int a0 = sg.kv_head * G;
-  float* o = out_o + ((size_t)sg.shard * Hq + a0) * Dv;
-  float* l = out_lse + (size_t)sg.shard * Hq + a0;
-  for (int i = threadIdx.x; i < G * Dv; i += kThreads) {
-    const int g = i / Dv, dv = i - g * Dv;
-    float top = -INFINITY;
-    for (int k = 0; k < sg.n_parts; ++k) top = fmaxf(top, ws_lse[(size_t)(sg.slot_begin + k) * G + g]);
-    float tot = 0.f, acc = 0.f;
-    for (int k = 0; k < sg.n_parts; ++k) {
-      const size_t slot = (size_t)(sg.slot_begin + k);
-      const float w = expf(ws_lse[slot * G + g] - top);
-      tot += w;
-      acc = fmaf(w, ws_o[(slot * G + g) * Dv + dv], acc);
+  const int q4 = Dv >> 2;
+  const int i4 = blockIdx.y * kThreads + threadIdx.x;
+  if (i4 >= G * q4) return;
+  const int g = i4 / q4;
+  const size_t row = (size_t)G * Dv;
+  float top = -INFINITY, tot = 0.f;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 < sg.n_parts; k0 += 8) {
+    float li[8];
+    float4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const size_t slot = (size_t)(sg.slot_begin + min(k0 + j, sg.n_parts - 1));
+      li[j] = ws_lse[slot * G + g];
+      v[j] = *(const float4*)(ws_o + slot * row + (size_t)i4 * 4);
     }
-    const bool empty = sg.n_parts == 0;
-    o[i] = empty ? 0.f : acc / tot;
-    if (dv == 0) l[g] = empty ? -INFINITY : top + logf(tot);
+    float bm = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (k0 + j >= sg.n_parts) li[j] = -INFINITY;
+      bm = fmaxf(bm, li[j]);
+    }
+    const float nt = fmaxf(top, bm);  // finite: tile partials are never empty
+    const float sc = expf(top - nt);
+    tot *= sc;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] *= sc;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bool live = li[j] != -INFINITY;
+      const float w = live ? expf(li[j] - nt) : 0.f;
+      tot += w;
+      acc[0] = fmaf(w, live ? v[j].x : 0.f, acc[0]);
+      acc[1] = fmaf(w, live ? v[j].y : 0.f, acc[1]);
+      acc[2] = fmaf(w, live ? v[j].z : 0.f, acc[2]);
+      acc[3] = fmaf(w, live ? v[j].w : 0.f, acc[3]);
+    }
+    top = nt;
   }
+  const bool empty = sg.n_parts == 0;
+  const float inv = empty ? 0.f : 1.f / tot;
+  float* o = out_o + ((size_t)sg.shard * Hq + (size_t)sg.kv_head * G) * Dv + (size_t)i4 * 4;
+  *(float4*)o = make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+  if ((i4 % q4) == 0) out_lse[(size_t)sg.shard * Hq + (size_t)sg.kv_head * G + g] = empty ? -INFINITY : top + logf(tot);
 }
 
 // Phase 4: per (output, head) merge of the partials named by the CSR lists.
@@ -184,13 +215,17 @@ nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_
     hipError_t e;
     if (plan->variant == kGeneric)
       e = launch_generic(d, p, plan->launch_blocks, st);
+    else if (plan->variant == kMlaMfmaBf16)
+      e = launch_mla_mfma(p, plan->launch_blocks, st);
     else
       e = launch_gqa_mfma(plan->variant, p, plan->launch_blocks, st);
     if (e != hipSuccess) return NANOCP_EHIP;
   }
   if (!plan->segs.empty()) {
-    hipLaunchKernelGGL(reduce_tiles_kernel, dim3((unsigned)plan->segs.size()), dim3(kThreads), 0, st, plan->d_segs,
-                       p.ws_o, p.ws_lse, out_o, out_lse, p.Hq, G, p.Dv);
+    if (p.Dv % 4) return NANOCP_ESHAPE;
+    const unsigned per_seg = (unsigned)((G * (p.Dv / 4) + kThreads - 1) / kThreads);
+    hipLaunchKernelGGL(reduce_tiles_kernel, dim3((unsigned)plan->segs.size(), per_seg), dim3(kThreads), 0, st,
+                       plan->d_segs, p.ws_o, p.ws_lse, out_o, out_lse, p.Hq, G, p.Dv);
     if (hipGetLastError() != hipSuccess) return NANOCP_EHIP;
   }
   return NANOCP_OK;

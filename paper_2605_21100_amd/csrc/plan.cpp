@@ -48,6 +48,9 @@ int pick_variant(const nanocp_attn_desc& d) {
     if (d.kv_dtype == NANOCP_BF16 && d.page_size == 64) return kGqaMfmaBf16;
     if (d.kv_dtype == NANOCP_FP8_E4M3 && d.page_size == 64) return kGqaMfmaFp8;
   }
+  if (d.kind == NANOCP_MLA && d.q_dtype == NANOCP_BF16 && d.kv_dtype == NANOCP_BF16 && d.num_q_heads == 128 &&
+      d.head_dim_qk == 576 && d.head_dim_v == 512 && d.page_size == 64)
+    return kMlaMfmaBf16;
   return kGeneric;
 }
 
@@ -101,6 +104,7 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
     const int Hkv = desc->num_kv_heads;
     const int G = desc->num_q_heads / Hkv;
     p->dynamic = p->variant != kGeneric;
+    p->fused = p->variant == kGqaMfmaBf16 || p->variant == kGqaMfmaFp8;
     const int c0 = env_int("NANOCP_PLAN_OVERHEAD_PAGES", 2, 0, 64);  // cost of a tile's Q load, combine, write-back
     const int min_pages = env_int("NANOCP_PLAN_MIN_PAGES", 8, 1, 1 << 20);
     const double static_frac = env_int("NANOCP_PLAN_STATIC_PCT", 85, 1, 100) / 100.0;
@@ -184,7 +188,7 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
       const int n = (int)(j - i);
       const int slot_begin = p->num_slots;
       if (n > 1) {
-        if (!p->dynamic) p->segs.push_back(Seg{p->tiles[i].shard, p->tiles[i].kv_head, slot_begin, n});
+        if (!p->fused) p->segs.push_back(Seg{p->tiles[i].shard, p->tiles[i].kv_head, slot_begin, n});
         for (size_t k = i; k < j; ++k) p->tiles[k].dst = p->num_slots++;
       }
       for (size_t k = i; k < j; ++k) {

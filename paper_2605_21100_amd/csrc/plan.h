@@ -71,7 +71,8 @@ struct nanocp_plan {
   std::vector<nanocp::Seg> segs;        // segments the separate reduce kernel handles
   int32_t num_multi_segs;               // (shard, head) pairs with more than one tile
   int32_t launch_blocks;                // workgroups to launch
-  bool dynamic;                         // workgroups pull chunks from a queue and reduce partials themselves
+  bool dynamic;                         // workgroups pull chunks from a queue
+  bool fused;                           // ... and reduce the tile partials of a (shard, head) themselves
   // device copy
   int device = -1;
   nanocp::DevTile* d_tiles = nullptr;
