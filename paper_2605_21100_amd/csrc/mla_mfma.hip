@@ -193,14 +193,12 @@ __global__ __launch_bounds__(kMlaThreads) __attribute__((amdgpu_waves_per_eu(2, 
       issue_page(pg0, 0);
       for (int pg = pg0; pg < pg1; ++pg) {
         const int buf = (pg - pg0) & 1;
-        if (pg + 1 < pg1) {
-          issue_page(pg + 1, buf ^ 1);
-          // the copies just issued may stay in flight; everything older (this page, Q) must have landed
-          asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kCopies) : "memory");
-        } else {
-          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        }
+        // this page's copy (issued one iteration ago, or before the loop) and, on the first page, Q have landed ...
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         wg_barrier();  // ... in every wavefront
+        // start the next page's copy; it overlaps this page's compute (its buffer was released by the barrier
+        // that ended the previous iteration)
+        if (pg + 1 < pg1) issue_page(pg + 1, buf ^ 1);
         const lds_ptr A = lds + buf * kBufBytes;
         const uint32_t boff = (uint32_t)(buf * kBufBytes);
         const uint32_t KA = K0 + boff, KBA = KB0 + boff, VA = V0 + boff;  // this buffer's lane bases
