@@ -80,13 +80,26 @@ __device__ inline void split8(const float* p, bf16x8& hi, bf16x8& lo) {
   hi = __builtin_bit_cast(bf16x8, h);
   lo = __builtin_bit_cast(bf16x8, l);
 }
+// Butterfly over the four 16-lane rows of a wavefront (lanes l, l^16, l^32, l^48 hold the same head) with the
+// row-swap instructions of the vector ALU (v_permlane16_swap / v_permlane32_swap) -- no trip through LDS.
+// swap16(x, x) = {rows x0 x0 x2 x2, rows x1 x1 x3 x3};  swap32(x, x) = {x0 x1 x0 x1, x2 x3 x2 x3}.
 __device__ inline float xor_max(float v) {
-  v = fmaxf(v, __shfl_xor(v, 16));
-  return fmaxf(v, __shfl_xor(v, 32));
+  typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+  const uint32_t u = __float_as_uint(v);
+  const u32x2_t a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float w = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const uint32_t uw = __float_as_uint(w);
+  const u32x2_t b = __builtin_amdgcn_permlane32_swap(uw, uw, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 __device__ inline float xor_sum(float v) {
-  v += __shfl_xor(v, 16);
-  return v + __shfl_xor(v, 32);
+  typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+  const uint32_t u = __float_as_uint(v);
+  const u32x2_t a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float w = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  const uint32_t uw = __float_as_uint(w);
+  const u32x2_t b = __builtin_amdgcn_permlane32_swap(uw, uw, false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
 __global__ __launch_bounds__(kMlaThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void mla_mfma_kernel(KParams p) {
