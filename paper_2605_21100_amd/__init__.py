@@ -45,6 +45,7 @@ EXPORTS = ["nanocp_plan_create", "nanocp_plan_query", "nanocp_plan_tiles", "nano
            "nanocp_decode_attn_partial_timed", "nanocp_merge_partials", "nanocp_status_str"]
 
 
+
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
@@ -225,3 +226,75 @@ class DeviceBatch:
         nanocp_decode_attn_partial(self.plan, self.q, self.k_pool, self.v_pool, self.k_scale, self.v_scale,
                                    self.block_table, self.out_o, self.out_lse, self.workspace, tile_clock)
         return self.out_o, self.out_lse
+
+
+# --------------------------------------------------------------------------- host scheduler (include/nanocp_sched.h)
+
+SCHED_MAX_CP = 8
+SCHED_EXPORTS = ["nanocp_sched_water_fill", "nanocp_sched_rebalance", "nanocp_sched_place"]
+
+
+class SchedConfig(ctypes.Structure):
+    _fields_ = [("num_nodes", ctypes.c_int32), ("node_offsets", ctypes.POINTER(ctypes.c_int32)),
+                ("kv_capacity", ctypes.c_int64), ("num_buckets", ctypes.c_int32),
+                ("bucket_max_len", ctypes.POINTER(ctypes.c_int64)), ("bucket_degree", ctypes.POINTER(ctypes.c_int32))]
+
+
+class SchedDecision(ctypes.Structure):
+    _fields_ = [("scheduled", ctypes.c_int32), ("node", ctypes.c_int32), ("moe_instance", ctypes.c_int32),
+                ("num_participants", ctypes.c_int32), ("participants", ctypes.c_int32 * SCHED_MAX_CP),
+                ("split", ctypes.c_int64 * SCHED_MAX_CP)]
+
+
+_lib.nanocp_sched_water_fill.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+_lib.nanocp_sched_rebalance.argtypes = [ctypes.POINTER(SchedConfig), ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_void_p, ctypes.c_void_p]
+_lib.nanocp_sched_place.argtypes = [ctypes.POINTER(SchedConfig), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                    ctypes.c_void_p, ctypes.POINTER(SchedDecision)]
+
+
+class Scheduler:
+    """Dual-balanced scheduler state for a cluster: nodes[n] = number of instances of node n."""
+
+    def __init__(self, instances_per_node, kv_capacity, bucket_max_len, bucket_degree):
+        self._offsets = np.concatenate([[0], np.cumsum(instances_per_node)]).astype(np.int32)
+        self._blen = np.ascontiguousarray(bucket_max_len, dtype=np.int64)
+        self._bdeg = np.ascontiguousarray(bucket_degree, dtype=np.int32)
+        self.num_instances = int(self._offsets[-1])
+        self.cfg = SchedConfig(len(instances_per_node), self._offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                               int(kv_capacity), len(self._blen),
+                               self._blen.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                               self._bdeg.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+        self.kv_load = np.zeros(self.num_instances, np.int64)
+        self.moe_load = np.zeros(self.num_instances, np.int32)
+
+    def rebalance(self, participants):
+        """participants: list of lists of instance ids (P_r of the active requests).  Returns m_r per request."""
+        offs = np.concatenate([[0], np.cumsum([len(p) for p in participants])]).astype(np.int32)
+        inst = np.asarray([s for p in participants for s in p], np.int32)
+        m = np.zeros(len(participants), np.int32)
+        _check(_lib.nanocp_sched_rebalance(ctypes.byref(self.cfg), len(participants), offs.ctypes.data,
+                                           inst.ctypes.data if len(inst) else None, m.ctypes.data,
+                                           self.moe_load.ctypes.data), "nanocp_sched_rebalance")
+        return m
+
+    def place(self, lengths):
+        lengths = np.ascontiguousarray(lengths, dtype=np.int64)
+        out = (SchedDecision * max(len(lengths), 1))()
+        _check(_lib.nanocp_sched_place(ctypes.byref(self.cfg), self.kv_load.ctypes.data, self.moe_load.ctypes.data,
+                                       len(lengths), lengths.ctypes.data, out), "nanocp_sched_place")
+        res = []
+        for i in range(len(lengths)):
+            d = out[i]
+            k = d.num_participants
+            res.append({"scheduled": bool(d.scheduled), "node": d.node, "m": d.moe_instance,
+                        "P": list(d.participants[:k]), "split": list(d.split[:k])})
+        return res
+
+
+def nanocp_sched_water_fill(loads, length):
+    loads = np.ascontiguousarray(loads, dtype=np.int64)
+    split = np.zeros(len(loads), np.int64)
+    _check(_lib.nanocp_sched_water_fill(len(loads), loads.ctypes.data, int(length), split.ctypes.data),
+           "nanocp_sched_water_fill")
+    return split.tolist()
