@@ -31,7 +31,9 @@ METRIC = "decode-attention KV GB/s (% of HBM peak) + µs/step, mixed ragged DCP 
 WORKLOAD_NAMES = {1: "config1: tiny fp32 GQA", 2: "config2: bf16 GQA 64 local requests U[1024,8192]",
                   3: "config3: mixed long-tail DCP batch, 128 requests lognormal(median 2048, sigma 1.2), bf16 GQA 64q/4kv d128",
                   4: "config4: MLA-absorbed bf16, 128 heads, 576/512, 64 requests U[4096,32768], half split CP=2",
-                  5: "config5: fp8 KV, 131072-token shard (CP=8 of 1,048,576) + 256 short requests"}
+                  5: "config5: fp8 KV, 131072-token shard (CP=8 of 1,048,576) + 256 short requests",
+                  6: "config6: the paper's micro-benchmark batch, 64 x 2048-token requests + a 1/8 slice of each of "
+                     "{n} 524288-token requests, bf16 GQA 64q/4kv d128"}
 
 
 def cpu_baseline(batch, budget_s=20.0):
@@ -68,6 +70,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--num-long", type=int, default=3, help="config 6 only: long requests per node (1, 3, 5, 7)")
     ap.add_argument("--tile-tokens", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-straggle", action="store_true")
@@ -100,7 +103,8 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_each_way": 1 << 30, "launches": 20, "ms_mean": float(ms.mean()),
                           "read_plus_write_GBs": 2 * (1 << 30) / (ms.mean() * 1e-3) / 1e9}))
         return
-    batch = W.FULL[args.config](with_remote_kv=False)
+    kw = {"num_long": args.num_long} if args.config == 6 else {}
+    batch = W.FULL[args.config](with_remote_kv=False, **kw)
     d = batch.desc
     db = nanocp.DeviceBatch(batch, tile_tokens=args.tile_tokens)
     pools = [(db.k_pool, db.v_pool, db.k_scale, db.v_scale)]
@@ -189,7 +193,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
         "dtype": {"f32": "f32", "bf16": "bf16", "fp8": "fp8_e4m3"}[d.kv_dtype], "data": "synthetic",
-        "config": {"workload": WORKLOAD_NAMES[args.config], "seed": int(batch.seed), "shard_entries": S,
+        "config": {"workload": WORKLOAD_NAMES[args.config].format(n=args.num_long), "seed": int(batch.seed), "shard_entries": S,
                    "requests": R, "local_kv_tokens": batch.local_tokens, "kv_bytes": kv_bytes,
                    "remote_partials": int(n_rem), "kernel": db.plan.kernel, "us_per_step": ms_per_step * 1e3,
                    "pct_of_hbm_peak": 100.0 * kv_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, **extra},

@@ -13,7 +13,7 @@ from parity import MERGE_VS_UNSHARDED_ABS, check_output
 
 pytestmark = pytest.mark.gpu
 
-EXPECTED_KERNEL = {1: "generic", 2: "gqa_mfma_bf16", 3: "gqa_mfma_bf16", 4: "mla_mfma_bf16", 5: "gqa_mfma_fp8"}
+EXPECTED_KERNEL = {1: "generic", 2: "gqa_mfma_bf16", 3: "gqa_mfma_bf16", 4: "mla_mfma_bf16", 5: "gqa_mfma_fp8", 6: "gqa_mfma_bf16"}
 
 
 def _say(msg):
@@ -33,7 +33,7 @@ def _merge_on_gpu(db, o_parts, lse_parts, out_dtype=torch.float32):
     return out, out_lse
 
 
-@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("tile_tokens", [0, 128, 448])
 def test_partial_and_merge_match_oracle(cid, tile_tokens):
     _say(f"[case] reduced config {cid} tile_tokens {tile_tokens}")
@@ -67,11 +67,11 @@ def test_partial_and_merge_match_oracle(cid, tile_tokens):
     db.plan.close()
 
 
-@pytest.mark.parametrize("cid", [1, 3, 4, 5])
+@pytest.mark.parametrize("cid", [1, 3, 4, 5, 6])
 def test_merged_equals_gpu_unsharded(cid):
     """The GPU's merge of its own d partials against the GPU's own single-shard run of the same request."""
     _say(f"[case] merged vs unsharded, reduced config {cid}")
-    b = W.reduced(cid, hold_all=True) if cid in (3, 5) else W.reduced(cid)
+    b = W.reduced(cid, hold_all=True) if cid in (3, 5, 6) else W.reduced(cid)
     assert len(b.remote_meta) == 0
     db = nanocp.DeviceBatch(b, tile_tokens=256 if b.desc.page_size <= 64 else 0)
     o, lse = db.partial()
@@ -216,7 +216,7 @@ def _sample_shards(b, k, rng):
     return sorted(pick)
 
 
-@pytest.mark.parametrize("cid", [2, 3, 4, 5])
+@pytest.mark.parametrize("cid", [2, 3, 4, 5, 6])
 def test_full_size_sampled(cid):
     """Full benchmark sizes in the launch configuration bench.py times (automatic tiling): sampled shard
     entries, always including the longest, checked one by one; every output finite."""

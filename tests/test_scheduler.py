@@ -168,3 +168,15 @@ def test_sched_argument_errors():
     with pytest.raises(nanocp.NanocpError) as e:
         nanocp.Scheduler([2, 2], 100, [10], [1]).place([-4])
     assert e.value.status == nanocp.EINVAL
+
+
+def test_micro_benchmark_split_is_what_the_scheduler_gives():
+    """Workload 6 hands each GPU an even 1/8 slice of every long request; that is the scheduler's own split
+    for the paper's micro-benchmark node (8 instances, each holding 64 x 2048 short tokens)."""
+    import workloads as W
+    sch = nanocp.Scheduler([8], 10 ** 9, [32768, 10 ** 12], [1, 8])
+    sch.kv_load[:] = 64 * 2048
+    out = sch.place([524288] * 3)
+    for d in out:
+        assert d["scheduled"] and sorted(d["P"]) == list(range(8)) and d["split"] == [65536] * 8
+    assert [e - b for b, e in W.even_split(524288, 8)] == [65536] * 8

@@ -1,4 +1,5 @@
-"""The five benchmark configurations as seeded generators, plus reduced variants for tests.
+"""The five benchmark configurations (and the paper's micro-benchmark batch as a sixth) as seeded
+generators, plus reduced variants for tests.
 
 Every full-size function takes optional overrides (request count, length range) so the
 parity tests can run the same recipe at sizes the float64 checker finishes in seconds.
@@ -109,7 +110,22 @@ def config5(seed=None, long_len=1048576, cp=8, held=3, num_short=256, lo=512, hi
     return build_batch("c5_fp8_long_shard", seed, _gqa_desc("fp8"), lengths, ranges, local, rng, with_remote_kv)
 
 
-FULL = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
+def config6(seed=None, num_long=3, long_len=524288, cp=8, held=5, num_short=64, short_len=2048,
+            with_remote_kv=True, hold_all=False):
+    """The paper's micro-benchmark batch (Evaluation, latency breakdown): `num_short` short requests of
+    `short_len` tokens local to this GPU plus, for each of `num_long` (1, 3, 5 or 7) long requests of the
+    node, this GPU's 1/cp slice.  All instances of the node carry the same short load, so the water-filling
+    split of a long request is the even one.  Requests 0..num_long-1 are the long ones.  bf16 GQA shapes."""
+    seed = BASE_SEED + 6 if seed is None else seed
+    rng = np.random.default_rng(seed)
+    lengths = np.array([long_len] * num_long + [short_len] * num_short, dtype=np.int64)
+    ranges = [even_split(long_len, cp) for _ in range(num_long)] + [[(0, short_len)] for _ in range(num_short)]
+    local = [list(range(cp)) if hold_all else [held] for _ in range(num_long)] + [[0] for _ in range(num_short)]
+    return build_batch(f"c6_micro_{num_long}x{long_len}", seed, _gqa_desc(), lengths, ranges, local, rng,
+                       with_remote_kv)
+
+
+FULL = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5, 6: config6}
 
 
 def reduced(config_id, with_remote_kv=True, hold_all=False):
@@ -127,5 +143,8 @@ def reduced(config_id, with_remote_kv=True, hold_all=False):
         return config4(num_requests=6, lo=200, hi=1500, with_remote_kv=with_remote_kv)
     if config_id == 5:
         return config5(long_len=40000, cp=8, held=3, num_short=20, lo=50, hi=700,
+                       with_remote_kv=with_remote_kv, hold_all=hold_all)
+    if config_id == 6:
+        return config6(num_long=3, long_len=20000, cp=8, held=5, num_short=10, short_len=333,
                        with_remote_kv=with_remote_kv, hold_all=hold_all)
     raise ValueError(config_id)
