@@ -204,6 +204,16 @@ def main():
                      "note": "events on the launch stream bracket nanocp_decode_attn_partial, which is one kernel "
                              "for the MFMA variants (tile kernel with fused tile reduction)"},
     }
+    if d.kind == "mla":
+        # MLA is co-limited: 2*(Dk+Dv)*Hq flop per token against Dk*2 bytes; the HBM term is the larger one at the
+        # published peaks, the matrix-core fraction is reported beside it (useful flops: the second bf16 term of P
+        # that the kernel also multiplies is not counted)
+        flops = 2.0 * (d.head_dim_qk + d.head_dim_v) * d.num_q_heads * batch.local_tokens
+        tf = flops / (part_ms.mean() * 1e-3) / 1e12
+        result["roofline"]["mfma"] = {"bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s",
+                                      "frac": tf / 2500.0}
+        result["roofline"]["note"] = ("events on the launch stream bracket nanocp_decode_attn_partial = the tile "
+                                      "kernel plus the tile-reduction kernel")
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(batch)
     print(json.dumps(result))

@@ -50,6 +50,8 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
                           "(or python paper_2605_21100_amd/build.py)")
+    import torch  # noqa: F401  -- first, so that the library binds to the HIP runtime torch has loaded (two
+    #                               runtimes in one process do not share devices, streams or memory)
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     lib.nanocp_plan_create.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(Shard), i32, i32, i32, i32, i32, i32,

@@ -105,9 +105,13 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
     const int G = desc->num_q_heads / Hkv;
     p->dynamic = p->variant != kGeneric;
     p->fused = p->variant == kGqaMfmaBf16 || p->variant == kGqaMfmaFp8;
-    const int c0 = env_int("NANOCP_PLAN_OVERHEAD_PAGES", 2, 0, 64);  // cost of a tile's Q load, combine, write-back
+    // An MLA tile is expensive (144 KB of Q in, a 256 KB partial out and back in through the reduction) and its
+    // pages cost the same compute everywhere, so the queue is all equal chunks; the GQA kernels are bandwidth-bound
+    // with timing that varies, so they keep a self-scheduled tail.  (Measured on the benchmark workloads.)
+    const bool mla = p->variant == kMlaMfmaBf16;
+    const int c0 = env_int("NANOCP_PLAN_OVERHEAD_PAGES", mla ? 6 : 2, 0, 64);  // cost of a tile's Q load, combine, write-back
     const int min_pages = env_int("NANOCP_PLAN_MIN_PAGES", 8, 1, 1 << 20);
-    const double static_frac = env_int("NANOCP_PLAN_STATIC_PCT", 85, 1, 100) / 100.0;
+    const double static_frac = env_int("NANOCP_PLAN_STATIC_PCT", mla ? 100 : 85, 1, 100) / 100.0;
     const int gss_k = env_int("NANOCP_PLAN_GSS_K", 2, 1, 64);
     const int64_t M = std::max<int64_t>(1, (int64_t)num_cus * env_int("NANOCP_PLAN_WGS_PER_CU", 1, 1, 16));
 
