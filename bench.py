@@ -33,7 +33,8 @@ WORKLOAD_NAMES = {1: "config1: tiny fp32 GQA", 2: "config2: bf16 GQA 64 local re
                   4: "config4: MLA-absorbed bf16, 128 heads, 576/512, 64 requests U[4096,32768], half split CP=2",
                   5: "config5: fp8 KV, 131072-token shard (CP=8 of 1,048,576) + 256 short requests",
                   6: "config6: the paper's micro-benchmark batch, 64 x 2048-token requests + a 1/8 slice of each of "
-                     "{n} 524288-token requests, bf16 GQA 64q/4kv d128"}
+                     "{n} 524288-token requests, bf16 GQA 64q/4kv d128",
+                  7: "config7: config 4's recipe with 64 query heads (MLA-absorbed bf16, 576/512)"}
 
 
 def cpu_baseline(batch, budget_s=20.0):

@@ -1,4 +1,4 @@
-// MFMA tile kernel for MLA-absorbed decode (DeepSeek-V3-like shapes): 128 query heads share one latent
+// MFMA tile kernel for MLA-absorbed decode (DeepSeek-V3-like shapes; 64 heads with 4 wavefronts): 128 query heads share one latent
 // row of 576 dims per token (512 latent + 64 rope); V is the first 512 dims of the same row, so a page is
 // read from HBM once and used for both products.  bf16, page size 64.
 // Paper: Data Plane, Phase 2 (partial attention + LSE over the local KV partition); the MoE-bound
@@ -31,12 +31,19 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kHq = 128, kDk = 576, kDv = 512, kPS = 64;
-constexpr int kMlaWaves = 8, kMlaThreads = 64 * kMlaWaves;
-constexpr int kHB = kHq / 16 / kMlaWaves;  // 16-head blocks per wavefront
-constexpr int kMasks = 16 / kMlaWaves;     // distinct swizzle masks among the token rows one wavefront copies
-constexpr int kSlabs = 8 / kMlaWaves;      // rope slabs (8 rows each) one wavefront copies
-constexpr int kCopies = kPS / kMlaWaves + kSlabs;  // direct-to-LDS loads per wavefront and page
+constexpr int kDk = 576, kDv = 512, kPS = 64;
+constexpr int kHB = 1;  // 16-head blocks per wavefront
+// kKD, kVD below: how far the LDS reads run ahead of the matrix instructions that use them (K: units of two
+// fragments, V: fragments); bounded by the registers left beside Q and the accumulators: (1, 2) with 256 registers
+// per wavefront.  Measured with 512 registers (64-head variant): going deeper than this does not help -- the
+// transpose read itself is the limit (about 100 B/clk per CU against 210 for 16-byte reads, measured with a
+// stand-alone probe), and it carries 64 KB per wavefront and page.
+#ifndef NANOCP_MLA64_KD
+#define NANOCP_MLA64_KD 2
+#endif
+#ifndef NANOCP_MLA64_VD
+#define NANOCP_MLA64_VD 4
+#endif
 constexpr int kRowBytes = kDk * 2;        // 1152: one token's latent row in HBM
 constexpr int kRowA = kDv * 2;            // 1024: dims 0..511 (the V part), LDS region A row
 constexpr int kRowB = (kDk - kDv) * 2;    // 128:  dims 512..575 (rope part), LDS region B row
@@ -102,7 +109,11 @@ __device__ inline float xor_sum(float v) {
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-__global__ __launch_bounds__(kMlaThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void mla_mfma_kernel(KParams p) {
+// kMlaWaves wavefronts of 16 heads each: 8 for 128 query heads (DeepSeek-V3-like), 4 for 64 (Kimi-K2-like)
+template <int kMlaWaves, int kKD, int kVD>
+__device__ __forceinline__ void mla_mfma_body(const KParams& p) {
+  constexpr int kHq = 16 * kHB * kMlaWaves;
+  constexpr int kSlabs = 8 / kMlaWaves;  // rope slabs (8 rows each) one wavefront copies
   extern __shared__ __attribute__((aligned(16))) char smem[];  // 2 page buffers
   __shared__ int next_s;
 
@@ -250,17 +261,18 @@ __global__ __launch_bounds__(kMlaThreads) __attribute__((amdgpu_waves_per_eu(2, 
           }
         };
         {
-          bf16x8 kf[2][2];
-          load_k(kf[0], 0);
+          bf16x8 kf[kKD + 1][2];
+#pragma unroll
+          for (int u = 0; u < kKD; ++u) load_k(kf[u], u);
 #pragma unroll
           for (int u = 0; u < 2 * kSteps; ++u) {
-            if (u + 1 < 2 * kSteps) load_k(kf[(u + 1) & 1], u + 1);
+            if (u + kKD < 2 * kSteps) load_k(kf[(u + kKD) % (kKD + 1)], u + kKD);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
               for (int hb = 0; hb < kHB; ++hb)
-                S[2 * (u & 1) + t2][hb] = mfma16(kf[u & 1][t2], qf[hb][u >> 1], S[2 * (u & 1) + t2][hb]);
+                S[2 * (u & 1) + t2][hb] = mfma16(kf[u % (kKD + 1)][t2], qf[hb][u >> 1], S[2 * (u & 1) + t2][hb]);
             __builtin_amdgcn_sched_barrier(0);
           }
         }
@@ -326,17 +338,17 @@ __global__ __launch_bounds__(kMlaThreads) __attribute__((amdgpu_waves_per_eu(2, 
         };
         {
           constexpr int kUnits = 2 * (kDv / 16);
-          bf16x8 vfr[3];
-          vfr[0] = load_v(0);
-          vfr[1] = load_v(1);
+          bf16x8 vfr[kVD + 1];
+#pragma unroll
+          for (int u = 0; u < kVD; ++u) vfr[u] = load_v(u);
 #pragma unroll
           for (int u = 0; u < kUnits; ++u) {
-            if (u + 2 < kUnits) vfr[(u + 2) % 3] = load_v(u + 2);
+            if (u + kVD < kUnits) vfr[(u + kVD) % (kVD + 1)] = load_v(u + kVD);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int hb = 0; hb < kHB; ++hb) acc[hb][u >> 1] = mfma16(vfr[u % 3], hi[hb][u & 1], acc[hb][u >> 1]);
+            for (int hb = 0; hb < kHB; ++hb) acc[hb][u >> 1] = mfma16(vfr[u % (kVD + 1)], hi[hb][u & 1], acc[hb][u >> 1]);
 #pragma unroll
-            for (int hb = 0; hb < kHB; ++hb) acc[hb][u >> 1] = mfma16(vfr[u % 3], lo[hb][u & 1], acc[hb][u >> 1]);
+            for (int hb = 0; hb < kHB; ++hb) acc[hb][u >> 1] = mfma16(vfr[u % (kVD + 1)], lo[hb][u & 1], acc[hb][u >> 1]);
             __builtin_amdgcn_sched_barrier(0);
           }
         }
@@ -388,13 +400,31 @@ __global__ __launch_bounds__(kMlaThreads) __attribute__((amdgpu_waves_per_eu(2, 
   }
 }
 
+// 128 heads: two wavefronts per SIMD, 256 registers each
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void mla_mfma_kernel(KParams p) {
+  mla_mfma_body<8, 1, 2>(p);
+}
+// 64 heads: one wavefront per SIMD, 512 registers: the LDS reads run far ahead
+__global__ __launch_bounds__(256, 1) void mla64_mfma_kernel(KParams p) {
+  mla_mfma_body<4, NANOCP_MLA64_KD, NANOCP_MLA64_VD>(p);
+}
+
 }  // namespace
 
 hipError_t launch_mla_mfma(const KParams& p, int num_blocks, hipStream_t st) {
-  static const hipError_t attr = hipFuncSetAttribute((const void*)mla_mfma_kernel,
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kBufBytes);
-  if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL(mla_mfma_kernel, dim3(num_blocks), dim3(kMlaThreads), 2 * kBufBytes, st, p);
+  if (p.Hq == 128) {
+    static const hipError_t attr = hipFuncSetAttribute((const void*)mla_mfma_kernel,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kBufBytes);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL(mla_mfma_kernel, dim3(num_blocks), dim3(512), 2 * kBufBytes, st, p);
+  } else if (p.Hq == 64) {
+    static const hipError_t attr = hipFuncSetAttribute((const void*)mla64_mfma_kernel,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kBufBytes);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL(mla64_mfma_kernel, dim3(num_blocks), dim3(256), 2 * kBufBytes, st, p);
+  } else {
+    return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

@@ -13,7 +13,7 @@ from parity import MERGE_VS_UNSHARDED_ABS, check_output
 
 pytestmark = pytest.mark.gpu
 
-EXPECTED_KERNEL = {1: "generic", 2: "gqa_mfma_bf16", 3: "gqa_mfma_bf16", 4: "mla_mfma_bf16", 5: "gqa_mfma_fp8", 6: "gqa_mfma_bf16"}
+EXPECTED_KERNEL = {1: "generic", 2: "gqa_mfma_bf16", 3: "gqa_mfma_bf16", 4: "mla_mfma_bf16", 5: "gqa_mfma_fp8", 6: "gqa_mfma_bf16", 7: "mla_mfma_bf16"}
 
 
 def _say(msg):
@@ -33,7 +33,7 @@ def _merge_on_gpu(db, o_parts, lse_parts, out_dtype=torch.float32):
     return out, out_lse
 
 
-@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5, 6, 7])
 @pytest.mark.parametrize("tile_tokens", [0, 128, 448])
 def test_partial_and_merge_match_oracle(cid, tile_tokens):
     _say(f"[case] reduced config {cid} tile_tokens {tile_tokens}")
@@ -67,7 +67,7 @@ def test_partial_and_merge_match_oracle(cid, tile_tokens):
     db.plan.close()
 
 
-@pytest.mark.parametrize("cid", [1, 3, 4, 5, 6])
+@pytest.mark.parametrize("cid", [1, 3, 4, 5, 6, 7])
 def test_merged_equals_gpu_unsharded(cid):
     """The GPU's merge of its own d partials against the GPU's own single-shard run of the same request."""
     _say(f"[case] merged vs unsharded, reduced config {cid}")
@@ -107,8 +107,8 @@ def _edge_batch(kv_dtype, shards_spec, seed=77):
     rng = np.random.default_rng(seed)
     if kv_dtype == "f32":
         desc = W.AttnDesc("gqa", "f32", "f32", 8, 2, 64, 64, 16, 0.125)
-    elif kv_dtype == "mla":
-        desc = W.AttnDesc("mla", "bf16", "bf16", 128, 1, 576, 512, 64, 192 ** -0.5)
+    elif kv_dtype in ("mla", "mla64"):
+        desc = W.AttnDesc("mla", "bf16", "bf16", 128 if kv_dtype == "mla" else 64, 1, 576, 512, 64, 192 ** -0.5)
     else:
         desc = W.AttnDesc("gqa", "bf16", kv_dtype, 64, 4, 128, 128, 64, 128 ** -0.5)
     lengths = [max(e, 1) for (_, e) in shards_spec]
@@ -119,7 +119,7 @@ def _edge_batch(kv_dtype, shards_spec, seed=77):
     return b
 
 
-@pytest.mark.parametrize("kv_dtype", ["f32", "bf16", "fp8", "mla"])
+@pytest.mark.parametrize("kv_dtype", ["f32", "bf16", "fp8", "mla", "mla64"])
 def test_edge_ranges(kv_dtype):
     """Empty shard, single token, ranges inside one page, starting / ending mid-page, exact page multiples."""
     _say(f"[case] edge ranges {kv_dtype}")
@@ -216,7 +216,7 @@ def _sample_shards(b, k, rng):
     return sorted(pick)
 
 
-@pytest.mark.parametrize("cid", [2, 3, 4, 5, 6])
+@pytest.mark.parametrize("cid", [2, 3, 4, 5, 6, 7])
 def test_full_size_sampled(cid):
     """Full benchmark sizes in the launch configuration bench.py times (automatic tiling): sampled shard
     entries, always including the longest, checked one by one; every output finite."""

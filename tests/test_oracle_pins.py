@@ -267,7 +267,7 @@ def test_page_permutation_invariance():
 
 # ---- the whole step on every reduced config: merged partials == unsharded attention (1e-12),
 #      CP=1 partial is already the final output, nothing is NaN although unused slots are NaN-filled
-@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5, 6, 7])
 def test_step_exactness_on_reduced_configs(cid):
     b = W.reduced(cid)
     O, LSE = oracle.local_partials(b)

@@ -70,7 +70,7 @@ def _check_partition(batch, plan, tile_tokens):
     return cost
 
 
-@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5, 6, 7])
 @pytest.mark.parametrize("tile_tokens", [0, 64, 256, 1024])
 def test_plan_partitions_reduced_configs(cid, tile_tokens):
     b = W.reduced(cid, with_remote_kv=False)

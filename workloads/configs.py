@@ -1,4 +1,4 @@
-"""The five benchmark configurations (and the paper's micro-benchmark batch as a sixth) as seeded
+"""The five benchmark configurations (the paper's micro-benchmark batch as a sixth, a 64-head MLA shape as a seventh) as seeded
 generators, plus reduced variants for tests.
 
 Every full-size function takes optional overrides (request count, length range) so the
@@ -79,12 +79,12 @@ def config3(seed=None, num_requests=128, median=2048, sigma=1.2, lo=16, hi=13107
     return build_batch("c3_mixed_dcp", seed, _gqa_desc(), lengths, ranges, local, rng, with_remote_kv)
 
 
-def config4(seed=None, num_requests=64, lo=4096, hi=32768, with_remote_kv=True):
+def config4(seed=None, num_requests=64, lo=4096, hi=32768, with_remote_kv=True, num_heads=128, name="c4_mla_bf16"):
     """MLA-absorbed decode: 128 heads over one 576-dim latent row per token (V = first 512 dims);
     every second request is split at CP=2 with both halves local and merged."""
     seed = BASE_SEED + 4 if seed is None else seed
     rng = np.random.default_rng(seed)
-    desc = AttnDesc("mla", "bf16", "bf16", 128, 1, 576, 512, 64, 1.0 / math.sqrt(192.0))
+    desc = AttnDesc("mla", "bf16", "bf16", num_heads, 1, 576, 512, 64, 1.0 / math.sqrt(192.0))
     lengths = rng.integers(lo, hi + 1, size=num_requests)
     ranges, local = [], []
     for r, L in enumerate(lengths):
@@ -94,7 +94,7 @@ def config4(seed=None, num_requests=64, lo=4096, hi=32768, with_remote_kv=True):
         else:
             ranges.append([(0, int(L))])
             local.append([0])
-    return build_batch("c4_mla_bf16", seed, desc, lengths, ranges, local, rng, with_remote_kv)
+    return build_batch(name, seed, desc, lengths, ranges, local, rng, with_remote_kv)
 
 
 def config5(seed=None, long_len=1048576, cp=8, held=3, num_short=256, lo=512, hi=4096, with_remote_kv=True,
@@ -125,7 +125,14 @@ def config6(seed=None, num_long=3, long_len=524288, cp=8, held=5, num_short=64, 
                        with_remote_kv)
 
 
-FULL = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5, 6: config6}
+def config7(seed=None, num_requests=64, lo=4096, hi=32768, with_remote_kv=True):
+    """Config 4's recipe with 64 query heads: the MLA shape of the paper's second model (its head count differs
+    from the first; the latent dims are taken to be the same 576/512, which the paper does not state)."""
+    return config4(BASE_SEED + 7 if seed is None else seed, num_requests, lo, hi, with_remote_kv, num_heads=64,
+                   name="c7_mla64_bf16")
+
+
+FULL = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5, 6: config6, 7: config7}
 
 
 def reduced(config_id, with_remote_kv=True, hold_all=False):
@@ -147,4 +154,6 @@ def reduced(config_id, with_remote_kv=True, hold_all=False):
     if config_id == 6:
         return config6(num_long=3, long_len=20000, cp=8, held=5, num_short=10, short_len=333,
                        with_remote_kv=with_remote_kv, hold_all=hold_all)
+    if config_id == 7:
+        return config7(num_requests=6, lo=200, hi=1500, with_remote_kv=with_remote_kv)
     raise ValueError(config_id)
