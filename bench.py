@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--num-long", type=int, default=3, help="config 6 only: long requests per node (1, 3, 5, 7)")
     ap.add_argument("--tile-tokens", type=int, default=0)
+    ap.add_argument("--merge-all", action="store_true",
+                    help="every output row goes through nanocp_merge_partials (default: requests whose only partial "
+                         "is a local shard are written in final form by the attention kernel itself)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-straggle", action="store_true")
     ap.add_argument("--dump-tiles", default="", help="write the tile list and per-tile device clocks to this .npz")
@@ -107,7 +110,7 @@ def main():
     kw = {"num_long": args.num_long} if args.config == 6 else {}
     batch = W.FULL[args.config](with_remote_kv=False, **kw)
     d = batch.desc
-    db = nanocp.DeviceBatch(batch, tile_tokens=args.tile_tokens)
+    db = nanocp.DeviceBatch(batch, tile_tokens=args.tile_tokens, final_rows=not args.merge_all)
     pools = [(db.k_pool, db.v_pool, db.k_scale, db.v_scale)]
     pools.append(tuple(None if t is None else t.clone() for t in pools[0]))
     S, R = batch.num_shards, batch.num_requests
@@ -124,16 +127,28 @@ def main():
     out = torch.empty((R, d.num_q_heads, d.head_dim_v), dtype=torch.bfloat16 if d.q_dtype == "bf16" else torch.float32,
                       device="cuda")
     local_o, local_lse = parts_o[:S], parts_lse[:S]
+    if not args.merge_all:
+        n_rest = len(db.rest_rows)
+        rest_offsets, rest_index = torch.from_numpy(db.rest_offsets).cuda(), torch.from_numpy(db.rest_index).cuda()
+        rest_rows = torch.from_numpy(db.rest_rows).cuda()
 
     def step(i, ev=None):
         k, v, ks, vs = pools[i & 1]
         if ev:
             ev[0].record()
-        nanocp.nanocp_decode_attn_partial(db.plan, db.q, k, v, ks, vs, db.block_table, local_o, local_lse,
-                                          db.workspace)
+        if args.merge_all:
+            nanocp.nanocp_decode_attn_partial(db.plan, db.q, k, v, ks, vs, db.block_table, local_o, local_lse,
+                                              db.workspace)
+        else:
+            nanocp.nanocp_decode_attn_partial(db.plan, db.q, k, v, ks, vs, db.block_table, local_o, local_lse,
+                                              db.workspace, final_out=out)
         if ev:
             ev[1].record()
-        nanocp.nanocp_merge_partials(db.desc, parts_o, parts_lse, part_offsets, part_index, R, out)
+        if args.merge_all:
+            nanocp.nanocp_merge_partials(db.desc, parts_o, parts_lse, part_offsets, part_index, R, out)
+        elif n_rest:
+            nanocp.nanocp_merge_partials(db.desc, parts_o, parts_lse, rest_offsets, rest_index, n_rest, out,
+                                         out_rows=rest_rows)
 
     for i in range(args.warmup):
         step(i)
@@ -196,7 +211,9 @@ def main():
         "dtype": {"f32": "f32", "bf16": "bf16", "fp8": "fp8_e4m3"}[d.kv_dtype], "data": "synthetic",
         "config": {"workload": WORKLOAD_NAMES[args.config].format(n=args.num_long), "seed": int(batch.seed), "shard_entries": S,
                    "requests": R, "local_kv_tokens": batch.local_tokens, "kv_bytes": kv_bytes,
-                   "remote_partials": int(n_rem), "kernel": db.plan.kernel, "us_per_step": ms_per_step * 1e3,
+                   "remote_partials": int(n_rem), "kernel": db.plan.kernel,
+                   "rows_final_from_kernel": 0 if args.merge_all else int((db.shard_final_row >= 0).sum()),
+                   "rows_merged": int(R) if args.merge_all else int(n_rest), "us_per_step": ms_per_step * 1e3,
                    "pct_of_hbm_peak": 100.0 * kv_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, **extra},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

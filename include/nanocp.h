@@ -176,6 +176,30 @@ nanocp_status nanocp_merge_partials(const nanocp_attn_desc* desc, const float* o
                                     const int32_t* part_offsets, const int32_t* part_index, int32_t num_out,
                                     void* out, int32_t out_dtype, float* out_lse, void* stream);
 
+/*
+ * Final rows without a merge (the paper's concern with per-step launch and copy overhead; Phase 4 is the identity
+ * for a request whose whole KV is on this instance).  nanocp_plan_set_final_rows (HOST, before nanocp_plan_upload):
+ * shard_final_row[s] = r >= 0 declares that shard s is the ONLY partial of output row r (r < num_out), -1 otherwise.
+ * nanocp_decode_attn_partial_final then writes, for those shards, the final row final_out[r] (NANOCP_F32 or
+ * NANOCP_BF16, [num_out, Hq, Dv], DEVICE, 16-byte aligned) and final_lse[r] ([num_out, Hq] float, may be NULL)
+ * straight from the kernel that finishes the shard; their out_o rows are NOT written (out_lse is).  All other shards
+ * behave as in nanocp_decode_attn_partial.  The remaining output rows are merged with nanocp_merge_partials_rows:
+ * like nanocp_merge_partials over num_out partial lists, list i producing row out_rows[i] (DEVICE int32, NULL =
+ * identity) of out / out_lse.
+ * Errors: as the calls they extend; ESTATE if the rows were not set (or set after upload), EBOUNDS for a row id
+ * outside [-1, num_out), ESHAPE if Dv is not a multiple of 8.
+ */
+nanocp_status nanocp_plan_set_final_rows(nanocp_plan* plan, const int32_t* shard_final_row, int32_t num_out);
+nanocp_status nanocp_decode_attn_partial_final(const nanocp_plan* plan, const void* q, const void* k_pool,
+                                               const void* v_pool, const float* k_scale, const float* v_scale,
+                                               const int32_t* block_table, float* out_o, float* out_lse,
+                                               void* workspace, size_t workspace_bytes, void* final_out,
+                                               int32_t final_dtype, float* final_lse, void* stream);
+nanocp_status nanocp_merge_partials_rows(const nanocp_attn_desc* desc, const float* o_parts, const float* lse_parts,
+                                         const int32_t* part_offsets, const int32_t* part_index, int32_t num_out,
+                                         const int32_t* out_rows, void* out, int32_t out_dtype, float* out_lse,
+                                         void* stream);
+
 const char* nanocp_status_str(nanocp_status s);
 
 #ifdef __cplusplus

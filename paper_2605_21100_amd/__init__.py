@@ -42,7 +42,8 @@ TILE_DTYPE = np.dtype([(n, np.int32) for n, _ in Tile._fields_])
 
 EXPORTS = ["nanocp_plan_create", "nanocp_plan_query", "nanocp_plan_tiles", "nanocp_plan_kernel",
            "nanocp_plan_upload", "nanocp_plan_destroy", "nanocp_decode_attn_partial",
-           "nanocp_decode_attn_partial_timed", "nanocp_merge_partials", "nanocp_status_str"]
+           "nanocp_decode_attn_partial_timed", "nanocp_merge_partials", "nanocp_status_str",
+           "nanocp_plan_set_final_rows", "nanocp_decode_attn_partial_final", "nanocp_merge_partials_rows"]
 
 
 
@@ -66,6 +67,9 @@ def _load():
     lib.nanocp_decode_attn_partial.argtypes = [vp] * 9 + [vp, sz, vp]
     lib.nanocp_decode_attn_partial_timed.argtypes = [vp] * 9 + [vp, sz, vp, vp]
     lib.nanocp_merge_partials.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, i32, vp, i32, vp, vp]
+    lib.nanocp_plan_set_final_rows.argtypes = [vp, vp, i32]
+    lib.nanocp_decode_attn_partial_final.argtypes = [vp] * 9 + [vp, sz, vp, i32, vp, vp]
+    lib.nanocp_merge_partials_rows.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, i32, vp, vp, i32, vp, vp]
     lib.nanocp_status_str.argtypes = [ctypes.c_int]
     lib.nanocp_status_str.restype = ctypes.c_char_p
     return lib
@@ -137,6 +141,13 @@ class Plan:
         buf = (ctypes.c_char * (n.value * ctypes.sizeof(Tile))).from_address(p.value)
         return np.frombuffer(buf, dtype=TILE_DTYPE).copy()
 
+    def set_final_rows(self, shard_final_row, num_out):
+        """shard_final_row[s] = r >= 0: shard s is the only partial of output row r (before upload)."""
+        rows = np.ascontiguousarray(shard_final_row, dtype=np.int32)
+        assert rows.shape == (self.num_shards,)
+        _check(_lib.nanocp_plan_set_final_rows(self._h, rows.ctypes.data, int(num_out)), "nanocp_plan_set_final_rows")
+        return self
+
     def upload(self, stream=None):
         _check(_lib.nanocp_plan_upload(self._h, _stream(stream)), "nanocp_plan_upload")
         self.uploaded = True
@@ -159,12 +170,21 @@ def nanocp_plan(desc, shards, num_q_rows, num_bt_rows, max_blocks_per_row, tile_
 
 
 def nanocp_decode_attn_partial(plan, q, k_pool, v_pool, k_scale, v_scale, block_table, out_o, out_lse,
-                               workspace, tile_clock=None, stream=None):
-    """Phase 2 on the given torch device tensors; results land in out_o / out_lse (float32)."""
+                               workspace, tile_clock=None, stream=None, final_out=None, final_lse=None):
+    """Phase 2 on the given torch device tensors; results land in out_o / out_lse (float32).  With final_out
+    (float32 or bfloat16 [num_out, Hq, Dv]) shards that are a whole output row write it directly."""
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     args = [plan._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(k_scale), _ptr(v_scale), _ptr(block_table),
             _ptr(out_o), _ptr(out_lse), _ptr(workspace), ws_bytes]
-    if tile_clock is None:
+    if final_out is not None:
+        import torch
+        assert tile_clock is None
+        if final_out.dtype not in (torch.bfloat16, torch.float32):
+            raise NanocpError(EUNSUPPORTED, "nanocp_decode_attn_partial_final")
+        _check(_lib.nanocp_decode_attn_partial_final(*args, _ptr(final_out), BF16 if final_out.dtype == torch.bfloat16
+                                                     else F32, _ptr(final_lse), _stream(stream)),
+               "nanocp_decode_attn_partial_final")
+    elif tile_clock is None:
         _check(_lib.nanocp_decode_attn_partial(*args, _stream(stream)), "nanocp_decode_attn_partial")
     else:
         _check(_lib.nanocp_decode_attn_partial_timed(*args, _ptr(tile_clock), _stream(stream)),
@@ -172,15 +192,40 @@ def nanocp_decode_attn_partial(plan, q, k_pool, v_pool, k_scale, v_scale, block_
 
 
 def nanocp_merge_partials(desc, o_parts, lse_parts, part_offsets, part_index, num_out, out, out_lse=None,
-                          stream=None):
-    """Phase 4 on device tensors; out is float32 or bfloat16 [num_out, Hq, Dv]."""
+                          stream=None, out_rows=None):
+    """Phase 4 on device tensors; out is float32 or bfloat16 [rows, Hq, Dv].  With out_rows (int32 [num_out]) list i
+    of the CSR produces row out_rows[i] instead of row i."""
     import torch
     out_dtype = BF16 if out.dtype == torch.bfloat16 else F32
     if out.dtype not in (torch.bfloat16, torch.float32):
         raise NanocpError(EUNSUPPORTED, "nanocp_merge_partials")
-    _check(_lib.nanocp_merge_partials(ctypes.byref(desc), _ptr(o_parts), _ptr(lse_parts), _ptr(part_offsets),
-                                      _ptr(part_index), num_out, _ptr(out), out_dtype, _ptr(out_lse),
-                                      _stream(stream)), "nanocp_merge_partials")
+    if out_rows is None:
+        _check(_lib.nanocp_merge_partials(ctypes.byref(desc), _ptr(o_parts), _ptr(lse_parts), _ptr(part_offsets),
+                                          _ptr(part_index), num_out, _ptr(out), out_dtype, _ptr(out_lse),
+                                          _stream(stream)), "nanocp_merge_partials")
+    else:
+        _check(_lib.nanocp_merge_partials_rows(ctypes.byref(desc), _ptr(o_parts), _ptr(lse_parts), _ptr(part_offsets),
+                                               _ptr(part_index), num_out, _ptr(out_rows), _ptr(out), out_dtype,
+                                               _ptr(out_lse), _stream(stream)), "nanocp_merge_partials_rows")
+
+
+def split_final_rows(part_offsets, part_index, num_local):
+    """Host helper.  From the pooled partial lists ([local shards | received partials], CSR per output row):
+    shard_final_row [num_local] (row r for a local shard that is the only partial of r, else -1) and the CSR
+    (offsets, index, rows) of the remaining rows, which still need nanocp_merge_partials."""
+    part_offsets = np.asarray(part_offsets, np.int64)
+    part_index = np.asarray(part_index, np.int64)
+    final = np.full(num_local, -1, np.int32)
+    offs, idx, rows = [0], [], []
+    for r in range(len(part_offsets) - 1):
+        parts = part_index[part_offsets[r]:part_offsets[r + 1]]
+        if len(parts) == 1 and parts[0] < num_local:
+            final[parts[0]] = r
+        else:
+            idx.extend(parts.tolist())
+            offs.append(len(idx))
+            rows.append(r)
+    return final, np.asarray(offs, np.int32), np.asarray(idx, np.int32), np.asarray(rows, np.int32)
 
 
 # --------------------------------------------------------------------------- convenience for tests / bench
@@ -206,7 +251,7 @@ def to_device(arr, kind=None, device="cuda"):
 class DeviceBatch:
     """A synthetic batch resident in HBM plus its plan, outputs and workspace."""
 
-    def __init__(self, batch, tile_tokens=0, num_cus=0, device="cuda"):
+    def __init__(self, batch, tile_tokens=0, num_cus=0, device="cuda", final_rows=False):
         import torch
         self.batch = batch
         d = batch.desc
@@ -219,7 +264,13 @@ class DeviceBatch:
         self.block_table = to_device(batch.block_table, device=device)
         S = batch.shards.shape[0]
         self.plan = Plan(self.desc, batch.shards, batch.q.shape[0], batch.block_table.shape[0],
-                         batch.block_table.shape[1], tile_tokens, num_cus).upload()
+                         batch.block_table.shape[1], tile_tokens, num_cus)
+        if final_rows:      # single-shard local requests skip the merge
+            fin, self.rest_offsets, self.rest_index, self.rest_rows = split_final_rows(
+                batch.part_offsets, batch.part_index, S)
+            self.plan.set_final_rows(fin, batch.num_requests)
+            self.shard_final_row = fin
+        self.plan.upload()
         self.out_o = torch.empty((S, d.num_q_heads, d.head_dim_v), dtype=torch.float32, device=device)
         self.out_lse = torch.empty((S, d.num_q_heads), dtype=torch.float32, device=device)
         self.workspace = torch.empty(max(self.plan.workspace_bytes, 16), dtype=torch.uint8, device=device)

@@ -27,7 +27,9 @@ __global__ __launch_bounds__(kThreads) void reduce_tiles_kernel(const Seg* __res
                                                                 const float* __restrict__ ws_o,
                                                                 const float* __restrict__ ws_lse,
                                                                 float* __restrict__ out_o, float* __restrict__ out_lse,
-                                                                int Hq, int G, int Dv) {
+                                                                void* __restrict__ final_out,
+                                                                float* __restrict__ final_lse, int final_bf16, int Hq,
+                                                                int G, int Dv) {
   const Seg sg = segs[blockIdx.x];
   const int q4 = Dv >> 2;
   const int i4 = blockIdx.y * kThreads + threadIdx.x;
@@ -70,9 +72,24 @@ __global__ __launch_bounds__(kThreads) void reduce_tiles_kernel(const Seg* __res
   }
   const bool empty = sg.n_parts == 0;
   const float inv = empty ? 0.f : 1.f / tot;
+  const float lse = empty ? -INFINITY : top + logf(tot);
+  if ((i4 % q4) == 0) out_lse[(size_t)sg.shard * Hq + (size_t)sg.kv_head * G + g] = lse;
+  if (final_out && sg.final_row >= 0) {
+    // the shard is the only partial of its output row: final form, no merge needed
+    const size_t fi = ((size_t)sg.final_row * Hq + (size_t)sg.kv_head * G) * Dv + (size_t)i4 * 4;
+    if (final_bf16) {
+      uint2 pk;
+      pk.x = (uint32_t)f32_to_bf16_rne(acc[0] * inv) | ((uint32_t)f32_to_bf16_rne(acc[1] * inv) << 16);
+      pk.y = (uint32_t)f32_to_bf16_rne(acc[2] * inv) | ((uint32_t)f32_to_bf16_rne(acc[3] * inv) << 16);
+      *(uint2*)((uint16_t*)final_out + fi) = pk;
+    } else {
+      *(float4*)((float*)final_out + fi) = make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+    }
+    if (final_lse && (i4 % q4) == 0) final_lse[(size_t)sg.final_row * Hq + (size_t)sg.kv_head * G + g] = lse;
+    return;
+  }
   float* o = out_o + ((size_t)sg.shard * Hq + (size_t)sg.kv_head * G) * Dv + (size_t)i4 * 4;
   *(float4*)o = make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
-  if ((i4 % q4) == 0) out_lse[(size_t)sg.shard * Hq + (size_t)sg.kv_head * G + g] = empty ? -INFINITY : top + logf(tot);
 }
 
 // Phase 4: per (output, head) merge of the partials named by the CSR lists.
@@ -81,10 +98,11 @@ template <bool kBf16Out>
 __global__ __launch_bounds__(kThreads) void merge_kernel(const float* __restrict__ o_parts,
                                                          const float* __restrict__ lse_parts,
                                                          const int32_t* __restrict__ part_offsets,
-                                                         const int32_t* __restrict__ part_index, void* __restrict__ out,
+                                                         const int32_t* __restrict__ part_index,
+                                                         const int32_t* __restrict__ out_rows, void* __restrict__ out,
                                                          float* __restrict__ out_lse, int Hq, int Dv) {
-  const int r = blockIdx.x;
-  const int b = part_offsets[r], e = part_offsets[r + 1];
+  const int b = part_offsets[blockIdx.x], e = part_offsets[blockIdx.x + 1];
+  const int r = out_rows ? out_rows[blockIdx.x] : (int)blockIdx.x;  // output row of this list
   const int q4 = Dv >> 2;  // float4 groups per head (Dv % 4 == 0 is checked by the host)
   const int i4 = blockIdx.y * kThreads + threadIdx.x;
   if (i4 >= Hq * q4) return;
@@ -167,8 +185,15 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float* __restrict
 
 nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_pool, const void* v_pool,
                           const float* k_scale, const float* v_scale, const int32_t* block_table, float* out_o,
-                          float* out_lse, void* workspace, size_t workspace_bytes, uint64_t* tile_clock, void* stream) {
+                          float* out_lse, void* workspace, size_t workspace_bytes, uint64_t* tile_clock, void* final_out,
+                          int32_t final_dtype, float* final_lse, void* stream) {
   if (!plan) return NANOCP_EINVAL;
+  if (final_out) {
+    if (final_dtype != NANOCP_F32 && final_dtype != NANOCP_BF16) return NANOCP_EUNSUPPORTED;
+    if (plan->num_final_rows == 0) return NANOCP_ESTATE;  // nanocp_plan_set_final_rows was not called
+    if ((uintptr_t)final_out & 15) return NANOCP_EINVAL;
+    if (plan->desc.head_dim_v % 8) return NANOCP_ESHAPE;
+  }
   const nanocp_attn_desc& d = plan->desc;
   if (plan->num_shards == 0) return NANOCP_OK;
   if (!q || !k_pool || !block_table || !out_o || !out_lse) return NANOCP_EINVAL;
@@ -201,6 +226,9 @@ nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_
   p.sync = plan->d_sync;
   p.num_chunks = plan->num_chunks;
   p.tile_clock = tile_clock;
+  p.final_out = final_out;
+  p.final_lse = final_out ? final_lse : nullptr;
+  p.final_bf16 = final_dtype == NANOCP_BF16;
   p.Hq = d.num_q_heads;
   p.Hkv = d.num_kv_heads;
   p.G = G;
@@ -225,7 +253,8 @@ nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_
     if (p.Dv % 4) return NANOCP_ESHAPE;
     const unsigned per_seg = (unsigned)((G * (p.Dv / 4) + kThreads - 1) / kThreads);
     hipLaunchKernelGGL(reduce_tiles_kernel, dim3((unsigned)plan->segs.size(), per_seg), dim3(kThreads), 0, st,
-                       plan->d_segs, p.ws_o, p.ws_lse, out_o, out_lse, p.Hq, G, p.Dv);
+                       plan->d_segs, p.ws_o, p.ws_lse, out_o, out_lse, p.final_out, p.final_lse, p.final_bf16, p.Hq, G,
+                       p.Dv);
     if (hipGetLastError() != hipSuccess) return NANOCP_EHIP;
   }
   return NANOCP_OK;
@@ -241,7 +270,17 @@ nanocp_status nanocp_decode_attn_partial(const nanocp_plan* plan, const void* q,
                                          const int32_t* block_table, float* out_o, float* out_lse, void* workspace,
                                          size_t workspace_bytes, void* stream) {
   return nanocp::run_partial(plan, q, k_pool, v_pool, k_scale, v_scale, block_table, out_o, out_lse, workspace,
-                             workspace_bytes, nullptr, stream);
+                             workspace_bytes, nullptr, nullptr, NANOCP_F32, nullptr, stream);
+}
+
+nanocp_status nanocp_decode_attn_partial_final(const nanocp_plan* plan, const void* q, const void* k_pool,
+                                               const void* v_pool, const float* k_scale, const float* v_scale,
+                                               const int32_t* block_table, float* out_o, float* out_lse,
+                                               void* workspace, size_t workspace_bytes, void* final_out,
+                                               int32_t final_dtype, float* final_lse, void* stream) {
+  if (!final_out) return NANOCP_EINVAL;
+  return nanocp::run_partial(plan, q, k_pool, v_pool, k_scale, v_scale, block_table, out_o, out_lse, workspace,
+                             workspace_bytes, nullptr, final_out, final_dtype, final_lse, stream);
 }
 
 nanocp_status nanocp_decode_attn_partial_timed(const nanocp_plan* plan, const void* q, const void* k_pool,
@@ -251,12 +290,20 @@ nanocp_status nanocp_decode_attn_partial_timed(const nanocp_plan* plan, const vo
                                                void* stream) {
   if (!tile_clock) return NANOCP_EINVAL;
   return nanocp::run_partial(plan, q, k_pool, v_pool, k_scale, v_scale, block_table, out_o, out_lse, workspace,
-                             workspace_bytes, tile_clock, stream);
+                             workspace_bytes, tile_clock, nullptr, NANOCP_F32, nullptr, stream);
 }
 
 nanocp_status nanocp_merge_partials(const nanocp_attn_desc* desc, const float* o_parts, const float* lse_parts,
                                     const int32_t* part_offsets, const int32_t* part_index, int32_t num_out, void* out,
                                     int32_t out_dtype, float* out_lse, void* stream) {
+  return nanocp_merge_partials_rows(desc, o_parts, lse_parts, part_offsets, part_index, num_out, nullptr, out, out_dtype,
+                                    out_lse, stream);
+}
+
+nanocp_status nanocp_merge_partials_rows(const nanocp_attn_desc* desc, const float* o_parts, const float* lse_parts,
+                                         const int32_t* part_offsets, const int32_t* part_index, int32_t num_out,
+                                         const int32_t* out_rows, void* out, int32_t out_dtype, float* out_lse,
+                                         void* stream) {
   if (!desc || num_out < 0) return NANOCP_EINVAL;
   if (desc->num_q_heads <= 0 || desc->head_dim_v <= 0) return NANOCP_EINVAL;
   if (out_dtype != NANOCP_F32 && out_dtype != NANOCP_BF16) return NANOCP_EUNSUPPORTED;
@@ -270,10 +317,10 @@ nanocp_status nanocp_merge_partials(const nanocp_attn_desc* desc, const float* o
   hipStream_t st = (hipStream_t)stream;
   if (out_dtype == NANOCP_BF16)
     hipLaunchKernelGGL((nanocp::merge_kernel<true>), grid, dim3(nanocp::kThreads), 0, st, o_parts, lse_parts,
-                       part_offsets, part_index, out, out_lse, Hq, Dv);
+                       part_offsets, part_index, out_rows, out, out_lse, Hq, Dv);
   else
     hipLaunchKernelGGL((nanocp::merge_kernel<false>), grid, dim3(nanocp::kThreads), 0, st, o_parts, lse_parts,
-                       part_offsets, part_index, out, out_lse, Hq, Dv);
+                       part_offsets, part_index, out_rows, out, out_lse, Hq, Dv);
   return hipGetLastError() == hipSuccess ? NANOCP_OK : NANOCP_EHIP;
 }
 

@@ -162,12 +162,31 @@ __global__ __launch_bounds__(kThreads) void generic_partial_kernel(KParams p) {
         dst_o = p.out_o + ((size_t)tile.shard * p.Hq + a0) * Dv;
         dst_l = p.out_lse + (size_t)tile.shard * p.Hq + a0;
       }
+      const bool fin = tile.dst < 0 && p.final_out && tile.final_row >= 0;  // the shard alone is an output row
+      if (fin) {
+        const size_t fo = ((size_t)tile.final_row * p.Hq + a0) * Dv;
 #pragma unroll
-      for (int i = 0; i < kAccPerThread; ++i) {
-        const int o = tid + i * kThreads;
-        if (o < GH * Dv) dst_o[o] = acc[i] / l_s[o / Dv];
+        for (int i = 0; i < kAccPerThread; ++i) {
+          const int o = tid + i * kThreads;
+          if (o < GH * Dv) {
+            const float v = acc[i] / l_s[o / Dv];
+            if (p.final_bf16) ((__bf16*)p.final_out)[fo + o] = (__bf16)v;
+            else ((float*)p.final_out)[fo + o] = v;
+          }
+        }
+        if (tid < GH) {
+          const float lse = m_s[tid] + logf(l_s[tid]);
+          dst_l[tid] = lse;
+          if (p.final_lse) p.final_lse[(size_t)tile.final_row * p.Hq + a0 + tid] = lse;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < kAccPerThread; ++i) {
+          const int o = tid + i * kThreads;
+          if (o < GH * Dv) dst_o[o] = acc[i] / l_s[o / Dv];
+        }
+        if (tid < GH) dst_l[tid] = m_s[tid] + logf(l_s[tid]);
       }
-      if (tid < GH) dst_l[tid] = m_s[tid] + logf(l_s[tid]);
     }
     if (p.tile_clock && tid == 0) {
       p.tile_clock[3 * (size_t)ti] = clk0;

@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
       const cptr<int32_t> w = tile_words + (size_t)ti * (sizeof(DevTile) / 4);
       tile.q_row = w[0], tile.bt_row = w[1], tile.kv_head = w[2], tile.shard = w[3];
       tile.tok_begin = w[4], tile.tok_end = w[5], tile.dst = w[6], tile.seg = w[7];
-      tile.n_parts = w[8], tile.slot_begin = w[9];
+      tile.n_parts = w[8], tile.slot_begin = w[9], tile.final_row = w[10];
     }
     uint64_t clk0 = 0;
     if (p.tile_clock && tid == 0) clk0 = wall_clock64();
@@ -438,10 +438,23 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
             o[4 + e] = fmaf(f[w], b[e], o[4 + e]);
           }
         }
-        float* dst_o = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG + n) * kD + d0;
-        *(f32x4*)dst_o = f32x4{o[0], o[1], o[2], o[3]};
-        *(f32x4*)(dst_o + 4) = f32x4{o[4], o[5], o[6], o[7]};
         if (c16 == 0) p.out_lse[(size_t)tile.shard * p.Hq + (size_t)h * kG + n] = lse_nat;
+        if (p.final_out && tile.final_row >= 0) {
+          // the shard alone is an output row: written in its final form, no merge needed
+          const size_t fo = ((size_t)tile.final_row * p.Hq + (size_t)h * kG + n) * kD + d0;
+          if (p.final_bf16) {
+            *(u32x4*)((__bf16*)p.final_out + fo) =
+                u32x4{pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]), pack_bf16(o[4], o[5]), pack_bf16(o[6], o[7])};
+          } else {
+            *(f32x4*)((float*)p.final_out + fo) = f32x4{o[0], o[1], o[2], o[3]};
+            *(f32x4*)((float*)p.final_out + fo + 4) = f32x4{o[4], o[5], o[6], o[7]};
+          }
+          if (c16 == 0 && p.final_lse) p.final_lse[(size_t)tile.final_row * p.Hq + (size_t)h * kG + n] = lse_nat;
+        } else {
+          float* dst_o = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG + n) * kD + d0;
+          *(f32x4*)dst_o = f32x4{o[0], o[1], o[2], o[3]};
+          *(f32x4*)(dst_o + 4) = f32x4{o[4], o[5], o[6], o[7]};
+        }
       } else {
         // one of several tiles: publish the partial, and let the workgroup that delivers the last one
         // LSE-combine them (same operator as the Phase 4 merge) into the shard's rows.  Here the thread owns
@@ -474,10 +487,21 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
             for (int e = 0; e < 8; ++e) r8[e] = fmaf(w, ld_dev(wo + (size_t)k * kG * kD + 16 * e), r8[e]);
           }
           const float rinv = 1.f / tot;
-          float* fo = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG + n) * kD + c16;
+          const float lse_f = top + logf(tot);
+          if (c16 == 0) p.out_lse[(size_t)tile.shard * p.Hq + (size_t)h * kG + n] = lse_f;
+          if (p.final_out && tile.final_row >= 0) {
+            const size_t fi = ((size_t)tile.final_row * p.Hq + (size_t)h * kG + n) * kD + c16;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) fo[16 * e] = r8[e] * rinv;
-          if (c16 == 0) p.out_lse[(size_t)tile.shard * p.Hq + (size_t)h * kG + n] = top + logf(tot);
+            for (int e = 0; e < 8; ++e) {
+              if (p.final_bf16) ((__bf16*)p.final_out)[fi + 16 * e] = (__bf16)(r8[e] * rinv);
+              else ((float*)p.final_out)[fi + 16 * e] = r8[e] * rinv;
+            }
+            if (c16 == 0 && p.final_lse) p.final_lse[(size_t)tile.final_row * p.Hq + (size_t)h * kG + n] = lse_f;
+          } else {
+            float* fo = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG + n) * kD + c16;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) fo[16 * e] = r8[e] * rinv;
+          }
           if (tid == 0) p.sync[kSyncSegBase + tile.seg] = 0;  // ready for the next launch
         }
       }

@@ -170,7 +170,7 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         const cptr<int32_t> w = tile_words + (size_t)ti * (sizeof(DevTile) / 4);
         tile.q_row = w[0], tile.bt_row = w[1], tile.kv_head = w[2], tile.shard = w[3];
         tile.tok_begin = w[4], tile.tok_end = w[5], tile.dst = w[6], tile.seg = w[7];
-        tile.n_parts = w[8], tile.slot_begin = w[9];
+        tile.n_parts = w[8], tile.slot_begin = w[9], tile.final_row = w[10];
       }
       uint64_t clk0 = 0;
       if (p.tile_clock && tid == 0) clk0 = wall_clock64();
@@ -366,18 +366,37 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         dst_o = p.out_o + (size_t)tile.shard * kHq * kDv;
         dst_l = p.out_lse + (size_t)tile.shard * kHq;
       }
+      const bool fin = tile.dst < 0 && p.final_out && tile.final_row >= 0;  // the shard alone is an output row
 #pragma unroll
       for (int hb = 0; hb < kHB; ++hb) {
         const float l = xor_sum(l_run[hb]);
         const float inv = 1.f / l;
         const int head = 16 * (kHB * wave + hb) + r;
-        float* orow = dst_o + (size_t)head * kDv + 4 * g;  // acc[hb][dvb][i] = dim 16dvb + 4g + i of that head
+        const float lse = (m_run[hb] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+        if (g == 0) dst_l[head] = lse;
+        if (fin) {
+          // acc[hb][dvb][i] = dim 16dvb + 4g + i of that head
+          const size_t fo = ((size_t)tile.final_row * kHq + head) * kDv + 4 * g;
 #pragma unroll
-        for (int dvb = 0; dvb < kDv / 16; ++dvb) {
-          *(f32x4*)(orow + 16 * dvb) = acc[hb][dvb] * inv;
-          if ((dvb & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+          for (int dvb = 0; dvb < kDv / 16; ++dvb) {
+            const f32x4 v = acc[hb][dvb] * inv;
+            if (p.final_bf16) {
+              u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+              *(u32x2*)((__bf16*)p.final_out + fo + 16 * dvb) = pk;
+            } else {
+              *(f32x4*)((float*)p.final_out + fo + 16 * dvb) = v;
+            }
+            if ((dvb & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+          }
+          if (g == 0 && p.final_lse) p.final_lse[(size_t)tile.final_row * kHq + head] = lse;
+        } else {
+          float* orow = dst_o + (size_t)head * kDv + 4 * g;  // acc[hb][dvb][i] = dim 16dvb + 4g + i of that head
+#pragma unroll
+          for (int dvb = 0; dvb < kDv / 16; ++dvb) {
+            *(f32x4*)(orow + 16 * dvb) = acc[hb][dvb] * inv;
+            if ((dvb & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+          }
         }
-        if (g == 0) dst_l[head] = (m_run[hb] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
       }
 
       if (p.tile_clock && tid == 0) {

@@ -192,20 +192,20 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
       const int n = (int)(j - i);
       const int slot_begin = p->num_slots;
       if (n > 1) {
-        if (!p->fused) p->segs.push_back(Seg{p->tiles[i].shard, p->tiles[i].kv_head, slot_begin, n});
+        if (!p->fused) p->segs.push_back(Seg{p->tiles[i].shard, p->tiles[i].kv_head, slot_begin, n, -1});
         for (size_t k = i; k < j; ++k) p->tiles[k].dst = p->num_slots++;
       }
       for (size_t k = i; k < j; ++k) {
         const nanocp_tile& t = p->tiles[k];
         p->dev_tiles[k] = DevTile{t.q_row, t.bt_row, t.kv_head, t.shard, t.tok_begin, t.tok_end, t.dst,
-                                  n > 1 ? p->num_multi_segs : -1, n, slot_begin, 0, 0};
+                                  n > 1 ? p->num_multi_segs : -1, n, slot_begin, -1, 0};
       }
       if (n > 1) p->num_multi_segs++;
       i = j;
     }
     for (int s = 0; s < num_shards; ++s)
       if (shards[s].kv_end == shards[s].kv_begin)
-        for (int h = 0; h < Hkv; ++h) p->segs.push_back(Seg{s, h, 0, 0});
+        for (int h = 0; h < Hkv; ++h) p->segs.push_back(Seg{s, h, 0, 0, -1});
 
     // Queue order: the statically sized chunks first, then the rest by decreasing cost (longest
     // processing time first), so that the very last chunks taken are the smallest ones.
@@ -259,6 +259,17 @@ nanocp_status nanocp_plan_tiles(const nanocp_plan* plan, const nanocp_tile** til
   if (!plan || !tiles || !num_tiles) return NANOCP_EINVAL;
   *tiles = plan->tiles.data();
   *num_tiles = (int32_t)plan->tiles.size();
+  return NANOCP_OK;
+}
+
+nanocp_status nanocp_plan_set_final_rows(nanocp_plan* plan, const int32_t* shard_final_row, int32_t num_out) {
+  if (!plan || !shard_final_row || num_out < 0) return NANOCP_EINVAL;
+  if (plan->device >= 0) return NANOCP_ESTATE;  // the device copy is immutable
+  for (int s = 0; s < plan->num_shards; ++s)
+    if (shard_final_row[s] < -1 || shard_final_row[s] >= num_out) return NANOCP_EBOUNDS;
+  for (nanocp::DevTile& t : plan->dev_tiles) t.final_row = shard_final_row[t.shard];
+  for (nanocp::Seg& sg : plan->segs) sg.final_row = shard_final_row[sg.shard];
+  plan->num_final_rows = num_out;
   return NANOCP_OK;
 }
 

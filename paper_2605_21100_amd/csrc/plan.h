@@ -16,6 +16,7 @@ struct Seg {
   int32_t kv_head;
   int32_t slot_begin;
   int32_t n_parts;
+  int32_t final_row;  // >= 0: the shard is the only partial of this output row (see nanocp_plan_set_final_rows)
 };
 
 constexpr int kThreads = 256;       // every kernel here runs 4 wavefronts per workgroup
@@ -28,7 +29,8 @@ struct DevTile {
   int32_t seg;         // index of the (shard, head)'s arrival counter (valid if dst >= 0)
   int32_t n_parts;     // tiles of this (shard, head)
   int32_t slot_begin;  // first partial slot of this (shard, head)
-  int32_t pad0, pad1;
+  int32_t final_row;   // >= 0: output row this shard alone produces (written in its final form), else -1
+  int32_t pad1;
 };
 
 // sync words owned by the plan (zero between launches): [0] work-queue head, [1] finished workgroups,
@@ -52,6 +54,9 @@ struct KParams {
   int32_t* sync;         // plan-owned counters (see kSyncSegBase)
   int32_t num_chunks;
   uint64_t* tile_clock;  // may be null
+  void* final_out;       // [num_out, Hq, Dv] float or bf16; null = every shard writes out_o / out_lse
+  float* final_lse;      // [num_out, Hq], may be null
+  int32_t final_bf16;
   int32_t Hq, Hkv, G, Dk, Dv, ps, max_blocks, kind;
   float scale;
 };
@@ -71,6 +76,7 @@ struct nanocp_plan {
   std::vector<nanocp::Seg> segs;        // segments the separate reduce kernel handles
   int32_t num_multi_segs;               // (shard, head) pairs with more than one tile
   int32_t launch_blocks;                // workgroups to launch
+  int32_t num_final_rows = 0;           // rows of the final output (0 = nanocp_plan_set_final_rows not called)
   bool dynamic;                         // workgroups pull chunks from a queue
   bool fused;                           // ... and reduce the tile partials of a (shard, head) themselves
   // device copy

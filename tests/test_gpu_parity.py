@@ -240,3 +240,69 @@ def test_full_size_sampled(cid):
     assert (o2 - o).abs().max().item() <= 1e-5 and (lse2 - lse).abs().max().item() <= 1e-5
     db.plan.close()
     db2.plan.close()
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("tile_tokens", [0, 128])
+def test_final_rows_equal_partial_plus_merge(cid, tile_tokens):
+    """Shards that are a whole output row write it in final form from the tile / reduction kernel; the rest goes
+    through the row-indexed merge.  The result must be bit-identical to partial + merge of the same plan shape
+    (same arithmetic, one cast), in f32 and bf16, and match the checker."""
+    _say(f"[case] final rows, reduced config {cid} tile_tokens {tile_tokens}")
+    b = W.reduced(cid)
+    ps = b.desc.page_size
+    tt = 0 if tile_tokens == 0 else max(ps, tile_tokens // ps * ps)
+    base = nanocp.DeviceBatch(b, tile_tokens=tt)
+    o, lse = base.partial()
+    rem_o, rem_lse = oracle.remote_partials(b)
+    rem_o_t = torch.from_numpy(rem_o.astype(np.float32)).cuda()
+    rem_lse_t = torch.from_numpy(rem_lse.astype(np.float32)).cuda()
+    want, want_lse = _merge_on_gpu(base, torch.cat([o, rem_o_t]), torch.cat([lse, rem_lse_t]))
+    S, R, d = b.num_shards, b.num_requests, b.desc
+    db = nanocp.DeviceBatch(b, tile_tokens=tt, final_rows=True)
+    assert (db.shard_final_row >= 0).sum() == sum(1 for r in range(R) if b.cp_degree[r] == 1)
+    for dt in (torch.float32, torch.bfloat16):
+        out = torch.full((R, d.num_q_heads, d.head_dim_v), float("nan"), dtype=dt, device="cuda")
+        out_lse = torch.full((R, d.num_q_heads), float("nan"), device="cuda")
+        parts_o = torch.cat([torch.full_like(o, float("nan")), rem_o_t])
+        parts_lse = torch.cat([torch.full_like(lse, float("nan")), rem_lse_t])
+        nanocp.nanocp_decode_attn_partial(db.plan, db.q, db.k_pool, db.v_pool, db.k_scale, db.v_scale, db.block_table,
+                                          parts_o[:S], parts_lse[:S], db.workspace, final_out=out, final_lse=out_lse)
+        n_rest = len(db.rest_rows)
+        if n_rest:
+            nanocp.nanocp_merge_partials(db.desc, parts_o, parts_lse, torch.from_numpy(db.rest_offsets).cuda(),
+                                         torch.from_numpy(db.rest_index).cuda(), n_rest, out, out_lse,
+                                         out_rows=torch.from_numpy(db.rest_rows).cuda())
+        torch.cuda.synchronize()
+        assert torch.equal(out, want.to(dt)), f"c{cid} {dt}"
+        assert torch.equal(out_lse, want_lse)
+        # per-shard LSE is still delivered for every shard; O rows of final shards are left alone
+        assert torch.equal(parts_lse[:S], lse)
+        fin = torch.from_numpy(db.shard_final_row >= 0).cuda()
+        assert torch.isnan(parts_o[:S][fin]).all() and torch.equal(parts_o[:S][~fin], o[~fin])
+    ref_o, ref_lse = oracle.local_partials(b)
+    ref_m, ref_mlse = oracle.merge_requests(np.concatenate([ref_o, rem_o]), np.concatenate([ref_lse, rem_lse]),
+                                            b.part_offsets, b.part_index)
+    check_output(b.desc, want.cpu().numpy(), want_lse.cpu().numpy(), ref_m, ref_mlse, f"c{cid} final rows")
+    base.plan.close()
+    db.plan.close()
+
+
+def test_final_rows_errors():
+    b = W.reduced(2)
+    db = nanocp.DeviceBatch(b)
+    d = b.desc
+    out = torch.empty((b.num_requests, d.num_q_heads, d.head_dim_v), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(nanocp.NanocpError) as e:        # rows were never declared
+        nanocp.nanocp_decode_attn_partial(db.plan, db.q, db.k_pool, db.v_pool, db.k_scale, db.v_scale, db.block_table,
+                                          db.out_o, db.out_lse, db.workspace, final_out=out)
+    assert e.value.status == nanocp.ESTATE
+    with pytest.raises(nanocp.NanocpError) as e:        # the uploaded plan is immutable
+        db.plan.set_final_rows(np.zeros(b.num_shards, np.int32), b.num_requests)
+    assert e.value.status == nanocp.ESTATE
+    plan = nanocp.Plan(db.desc, b.shards, b.q.shape[0], b.block_table.shape[0], b.block_table.shape[1])
+    with pytest.raises(nanocp.NanocpError) as e:
+        plan.set_final_rows(np.full(b.num_shards, b.num_requests, np.int32), b.num_requests)
+    assert e.value.status == nanocp.EBOUNDS
+    plan.close()
+    db.plan.close()
