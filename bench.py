@@ -212,7 +212,7 @@ def main():
         "config": {"workload": WORKLOAD_NAMES[args.config].format(n=args.num_long), "seed": int(batch.seed), "shard_entries": S,
                    "requests": R, "local_kv_tokens": batch.local_tokens, "kv_bytes": kv_bytes,
                    "remote_partials": int(n_rem), "kernel": db.plan.kernel,
-                   "rows_final_from_kernel": 0 if args.merge_all else int((db.shard_final_row >= 0).sum()),
+                   "rows_final_from_kernel": 0 if args.merge_all else int(len(set(db.shard_final_row[db.shard_final_row >= 0].tolist()))),
                    "rows_merged": int(R) if args.merge_all else int(n_rest), "us_per_step": ms_per_step * 1e3,
                    "pct_of_hbm_peak": 100.0 * kv_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, **extra},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

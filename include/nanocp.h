@@ -179,11 +179,14 @@ nanocp_status nanocp_merge_partials(const nanocp_attn_desc* desc, const float* o
 /*
  * Final rows without a merge (the paper's concern with per-step launch and copy overhead; Phase 4 is the identity
  * for a request whose whole KV is on this instance).  nanocp_plan_set_final_rows (HOST, before nanocp_plan_upload):
- * shard_final_row[s] = r >= 0 declares that shard s is the ONLY partial of output row r (r < num_out), -1 otherwise.
- * nanocp_decode_attn_partial_final then writes, for those shards, the final row final_out[r] (NANOCP_F32 or
+ * shard_final_row[s] = r >= 0 declares that every partial of output row r (r < num_out) is a shard of this plan and
+ * s is one of them (usually the only one; several shards may name the same row -- a request split over shards that
+ * are all local -- and are then reduced together), -1 otherwise.  The call re-derives the partial slots: query the
+ * workspace size after it.  nanocp_decode_attn_partial_final then writes the final row final_out[r] (NANOCP_F32 or
  * NANOCP_BF16, [num_out, Hq, Dv], DEVICE, 16-byte aligned) and final_lse[r] ([num_out, Hq] float, may be NULL)
- * straight from the kernel that finishes the shard; their out_o rows are NOT written (out_lse is).  All other shards
- * behave as in nanocp_decode_attn_partial.  The remaining output rows are merged with nanocp_merge_partials_rows:
+ * straight from the kernel that finishes it; the out_o rows of those shards are NOT written (out_lse is, but means
+ * the row's LSE when shards share a row, and a plan with such shards only runs through this entry point).  All
+ * other shards behave as in nanocp_decode_attn_partial.  The remaining output rows are merged with nanocp_merge_partials_rows:
  * like nanocp_merge_partials over num_out partial lists, list i producing row out_rows[i] (DEVICE int32, NULL =
  * identity) of out / out_lse.
  * Errors: as the calls they extend; ESTATE if the rows were not set (or set after upload), EBOUNDS for a row id

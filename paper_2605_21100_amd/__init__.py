@@ -122,11 +122,14 @@ class Plan:
         _check(_lib.nanocp_plan_create(ctypes.byref(desc), sp, self.num_shards, num_q_rows, num_bt_rows,
                                        max_blocks_per_row, tile_tokens, num_cus, ctypes.byref(self._h)),
                "nanocp_plan_create")
+        self._query()
+        self.uploaded = False
+
+    def _query(self):
         nt, nc, ws = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_size_t()
         _check(_lib.nanocp_plan_query(self._h, ctypes.byref(nt), ctypes.byref(nc), ctypes.byref(ws)),
                "nanocp_plan_query")
         self.num_tiles, self.num_chunks, self.workspace_bytes = nt.value, nc.value, ws.value
-        self.uploaded = False
 
     @property
     def kernel(self):
@@ -146,6 +149,7 @@ class Plan:
         rows = np.ascontiguousarray(shard_final_row, dtype=np.int32)
         assert rows.shape == (self.num_shards,)
         _check(_lib.nanocp_plan_set_final_rows(self._h, rows.ctypes.data, int(num_out)), "nanocp_plan_set_final_rows")
+        self._query()       # the partial slots (workspace size) were re-derived
         return self
 
     def upload(self, stream=None):
@@ -209,18 +213,19 @@ def nanocp_merge_partials(desc, o_parts, lse_parts, part_offsets, part_index, nu
                                                _ptr(out_lse), _stream(stream)), "nanocp_merge_partials_rows")
 
 
-def split_final_rows(part_offsets, part_index, num_local):
+def split_final_rows(part_offsets, part_index, num_local, single_only=False):
     """Host helper.  From the pooled partial lists ([local shards | received partials], CSR per output row):
-    shard_final_row [num_local] (row r for a local shard that is the only partial of r, else -1) and the CSR
-    (offsets, index, rows) of the remaining rows, which still need nanocp_merge_partials."""
+    shard_final_row [num_local] (row r for the local shards of a row all of whose partials are local -- with
+    single_only, only rows with exactly one partial -- else -1) and the CSR (offsets, index, rows) of the
+    remaining rows, which still need nanocp_merge_partials."""
     part_offsets = np.asarray(part_offsets, np.int64)
     part_index = np.asarray(part_index, np.int64)
     final = np.full(num_local, -1, np.int32)
     offs, idx, rows = [0], [], []
     for r in range(len(part_offsets) - 1):
         parts = part_index[part_offsets[r]:part_offsets[r + 1]]
-        if len(parts) == 1 and parts[0] < num_local:
-            final[parts[0]] = r
+        if len(parts) >= 1 and (parts < num_local).all() and (len(parts) == 1 or not single_only):
+            final[parts] = r
         else:
             idx.extend(parts.tolist())
             offs.append(len(idx))
@@ -251,7 +256,7 @@ def to_device(arr, kind=None, device="cuda"):
 class DeviceBatch:
     """A synthetic batch resident in HBM plus its plan, outputs and workspace."""
 
-    def __init__(self, batch, tile_tokens=0, num_cus=0, device="cuda", final_rows=False):
+    def __init__(self, batch, tile_tokens=0, num_cus=0, device="cuda", final_rows=False, single_only=False):
         import torch
         self.batch = batch
         d = batch.desc
@@ -267,7 +272,7 @@ class DeviceBatch:
                          batch.block_table.shape[1], tile_tokens, num_cus)
         if final_rows:      # single-shard local requests skip the merge
             fin, self.rest_offsets, self.rest_index, self.rest_rows = split_final_rows(
-                batch.part_offsets, batch.part_index, S)
+                batch.part_offsets, batch.part_index, S, single_only)
             self.plan.set_final_rows(fin, batch.num_requests)
             self.shard_final_row = fin
         self.plan.upload()

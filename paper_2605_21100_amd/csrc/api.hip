@@ -194,6 +194,7 @@ nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_
     if ((uintptr_t)final_out & 15) return NANOCP_EINVAL;
     if (plan->desc.head_dim_v % 8) return NANOCP_ESHAPE;
   }
+  if (plan->grouped && !final_out) return NANOCP_ESTATE;  // grouped shards have no per-shard result to deliver
   const nanocp_attn_desc& d = plan->desc;
   if (plan->num_shards == 0) return NANOCP_OK;
   if (!q || !k_pool || !block_table || !out_o || !out_lse) return NANOCP_EINVAL;

@@ -64,6 +64,65 @@ int env_int(const char* name, int dflt, int lo, int hi) {
   return (int)std::min<long>(hi, std::max<long>(lo, x));
 }
 
+// Partial slots and reduction segments.  A segment is the set of tiles whose partials combine into one result:
+// the tiles of one (shard, kv head), or -- when final_row names the same output row for several shards (all the
+// partials of that row are local) -- of all those shards together, so that the row needs no merge afterwards.
+// A segment with one tile writes its result directly (dst = -1); otherwise its tiles get consecutive slots.
+void assign_segments(nanocp_plan* p, const int32_t* final_row) {
+  const int Hkv = p->desc.num_kv_heads;
+  const int G = p->desc.num_q_heads / Hkv;
+  const int S = p->num_shards;
+  // group id of a shard: the first shard naming the same output row, or itself
+  std::vector<int> group(S), first_of_row;
+  for (int s = 0; s < S; ++s) {
+    group[s] = s;
+    if (final_row && final_row[s] >= 0) {
+      if ((size_t)final_row[s] >= first_of_row.size()) first_of_row.resize(final_row[s] + 1, -1);
+      if (first_of_row[final_row[s]] < 0) first_of_row[final_row[s]] = s;
+      group[s] = first_of_row[final_row[s]];
+    }
+  }
+  std::vector<int> count((size_t)S * Hkv, 0), slot0((size_t)S * Hkv, 0), seg_id((size_t)S * Hkv, -1), next((size_t)S * Hkv, 0);
+  for (const nanocp_tile& t : p->tiles) count[(size_t)group[t.shard] * Hkv + t.kv_head]++;
+  p->num_slots = 0;
+  p->num_multi_segs = 0;
+  p->segs.clear();
+  p->grouped = false;
+  for (int s = 0; s < S; ++s) {
+    if (group[s] != s) {
+      p->grouped = true;
+      continue;
+    }
+    for (int h = 0; h < Hkv; ++h) {
+      const size_t key = (size_t)s * Hkv + h;
+      const int n = count[key];
+      const int fr = final_row ? final_row[s] : -1;
+      if (n > 1) {
+        slot0[key] = p->num_slots;
+        p->num_slots += n;
+        seg_id[key] = p->num_multi_segs++;
+        if (!p->fused) p->segs.push_back(nanocp::Seg{s, h, slot0[key], n, fr});
+      } else if (n == 0) {
+        p->segs.push_back(nanocp::Seg{s, h, 0, 0, fr});  // nothing to attend to: O = 0, LSE = -inf
+      }
+    }
+  }
+  // members of a group that are not its first shard have no result of their own; an empty one that is alone is
+  // covered above (it is its own group)
+  for (size_t i = 0; i < p->tiles.size(); ++i) {
+    nanocp_tile& t = p->tiles[i];
+    const size_t key = (size_t)group[t.shard] * Hkv + t.kv_head;
+    const int n = count[key];
+    t.dst = n > 1 ? slot0[key] + next[key]++ : -1;
+    p->dev_tiles[i] = nanocp::DevTile{t.q_row, t.bt_row, t.kv_head, t.shard, t.tok_begin, t.tok_end, t.dst,
+                                      seg_id[key], n, slot0[key], final_row ? final_row[t.shard] : -1, 0};
+  }
+  // workspace: o partials [slots, G, Dv] then lse partials [slots, G], each 256-byte aligned
+  const size_t o_bytes = ((size_t)p->num_slots * G * p->desc.head_dim_v * sizeof(float) + 255) & ~(size_t)255;
+  const size_t l_bytes = ((size_t)p->num_slots * G * sizeof(float) + 255) & ~(size_t)255;
+  p->workspace_bytes = p->num_slots ? o_bytes + l_bytes : 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -182,30 +241,8 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
     }
     p->launch_blocks = p->dynamic ? (int32_t)std::min<int64_t>(p->num_chunks, M) : p->num_chunks;
 
-    // partial slots and reduction segments: tiles of one (shard, head) are consecutive in the list
-    p->num_slots = 0;
-    p->num_multi_segs = 0;
     p->dev_tiles.resize(p->tiles.size());
-    for (size_t i = 0; i < p->tiles.size();) {
-      size_t j = i;
-      while (j < p->tiles.size() && p->tiles[j].shard == p->tiles[i].shard && p->tiles[j].kv_head == p->tiles[i].kv_head) ++j;
-      const int n = (int)(j - i);
-      const int slot_begin = p->num_slots;
-      if (n > 1) {
-        if (!p->fused) p->segs.push_back(Seg{p->tiles[i].shard, p->tiles[i].kv_head, slot_begin, n, -1});
-        for (size_t k = i; k < j; ++k) p->tiles[k].dst = p->num_slots++;
-      }
-      for (size_t k = i; k < j; ++k) {
-        const nanocp_tile& t = p->tiles[k];
-        p->dev_tiles[k] = DevTile{t.q_row, t.bt_row, t.kv_head, t.shard, t.tok_begin, t.tok_end, t.dst,
-                                  n > 1 ? p->num_multi_segs : -1, n, slot_begin, -1, 0};
-      }
-      if (n > 1) p->num_multi_segs++;
-      i = j;
-    }
-    for (int s = 0; s < num_shards; ++s)
-      if (shards[s].kv_end == shards[s].kv_begin)
-        for (int h = 0; h < Hkv; ++h) p->segs.push_back(Seg{s, h, 0, 0, -1});
+    assign_segments(p, nullptr);
 
     // Queue order: the statically sized chunks first, then the rest by decreasing cost (longest
     // processing time first), so that the very last chunks taken are the smallest ones.
@@ -234,10 +271,6 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
     p->chunk_offsets.assign(p->num_chunks + 1, 0);
     for (const nanocp_tile& t : p->tiles) p->chunk_offsets[t.chunk + 1]++;
     for (int c = 0; c < p->num_chunks; ++c) p->chunk_offsets[c + 1] += p->chunk_offsets[c];
-    // workspace: o partials [slots, G, Dv] then lse partials [slots, G], each 256-byte aligned
-    const size_t o_bytes = ((size_t)p->num_slots * G * desc->head_dim_v * sizeof(float) + 255) & ~(size_t)255;
-    const size_t l_bytes = ((size_t)p->num_slots * G * sizeof(float) + 255) & ~(size_t)255;
-    p->workspace_bytes = p->num_slots ? o_bytes + l_bytes : 0;
   } catch (const std::bad_alloc&) {
     delete p;
     return NANOCP_ENOMEM;
@@ -267,8 +300,11 @@ nanocp_status nanocp_plan_set_final_rows(nanocp_plan* plan, const int32_t* shard
   if (plan->device >= 0) return NANOCP_ESTATE;  // the device copy is immutable
   for (int s = 0; s < plan->num_shards; ++s)
     if (shard_final_row[s] < -1 || shard_final_row[s] >= num_out) return NANOCP_EBOUNDS;
-  for (nanocp::DevTile& t : plan->dev_tiles) t.final_row = shard_final_row[t.shard];
-  for (nanocp::Seg& sg : plan->segs) sg.final_row = shard_final_row[sg.shard];
+  try {
+    assign_segments(plan, shard_final_row);
+  } catch (const std::bad_alloc&) {
+    return NANOCP_ENOMEM;
+  }
   plan->num_final_rows = num_out;
   return NANOCP_OK;
 }

@@ -77,6 +77,7 @@ struct nanocp_plan {
   int32_t num_multi_segs;               // (shard, head) pairs with more than one tile
   int32_t launch_blocks;                // workgroups to launch
   int32_t num_final_rows = 0;           // rows of the final output (0 = nanocp_plan_set_final_rows not called)
+  bool grouped = false;                 // some output row is fed by several local shards reduced as one segment
   bool dynamic;                         // workgroups pull chunks from a queue
   bool fused;                           // ... and reduce the tile partials of a (shard, head) themselves
   // device copy

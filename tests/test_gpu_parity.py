@@ -244,7 +244,8 @@ def test_full_size_sampled(cid):
 
 @pytest.mark.parametrize("cid", [1, 2, 3, 4, 5, 6, 7])
 @pytest.mark.parametrize("tile_tokens", [0, 128])
-def test_final_rows_equal_partial_plus_merge(cid, tile_tokens):
+@pytest.mark.parametrize("single_only", [False, True])
+def test_final_rows_equal_partial_plus_merge(cid, tile_tokens, single_only):
     """Shards that are a whole output row write it in final form from the tile / reduction kernel; the rest goes
     through the row-indexed merge.  The result must be bit-identical to partial + merge of the same plan shape
     (same arithmetic, one cast), in f32 and bf16, and match the checker."""
@@ -259,8 +260,12 @@ def test_final_rows_equal_partial_plus_merge(cid, tile_tokens):
     rem_lse_t = torch.from_numpy(rem_lse.astype(np.float32)).cuda()
     want, want_lse = _merge_on_gpu(base, torch.cat([o, rem_o_t]), torch.cat([lse, rem_lse_t]))
     S, R, d = b.num_shards, b.num_requests, b.desc
-    db = nanocp.DeviceBatch(b, tile_tokens=tt, final_rows=True)
-    assert (db.shard_final_row >= 0).sum() == sum(1 for r in range(R) if b.cp_degree[r] == 1)
+    db = nanocp.DeviceBatch(b, tile_tokens=tt, final_rows=True, single_only=single_only)
+    n_local = np.array([(b.part_index[b.part_offsets[r]:b.part_offsets[r + 1]] < S).sum() for r in range(R)])
+    all_local = n_local == np.diff(b.part_offsets)
+    assert (db.shard_final_row >= 0).sum() == int(n_local[all_local & ((n_local == 1) | (not single_only))].sum())
+    grouped = not single_only and bool((all_local & (n_local > 1)).any())
+    assert grouped == (cid in (1, 4, 7) and not single_only)
     for dt in (torch.float32, torch.bfloat16):
         out = torch.full((R, d.num_q_heads, d.head_dim_v), float("nan"), dtype=dt, device="cuda")
         out_lse = torch.full((R, d.num_q_heads), float("nan"), device="cuda")
@@ -274,11 +279,21 @@ def test_final_rows_equal_partial_plus_merge(cid, tile_tokens):
                                          torch.from_numpy(db.rest_index).cuda(), n_rest, out, out_lse,
                                          out_rows=torch.from_numpy(db.rest_rows).cuda())
         torch.cuda.synchronize()
-        assert torch.equal(out, want.to(dt)), f"c{cid} {dt}"
-        assert torch.equal(out_lse, want_lse)
-        # per-shard LSE is still delivered for every shard; O rows of final shards are left alone
-        assert torch.equal(parts_lse[:S], lse)
         fin = torch.from_numpy(db.shard_final_row >= 0).cuda()
+        if not grouped:
+            assert torch.equal(out, want.to(dt)), f"c{cid} {dt}"
+            assert torch.equal(out_lse, want_lse)
+            # per-shard LSE is still delivered for every shard
+            assert torch.equal(parts_lse[:S], lse)
+        else:
+            # shards of one row reduced as one segment: same operator, different association -> fp32 rounding
+            err = (out.float() - want).abs()
+            if dt == torch.float32:
+                assert err.max().item() <= 1e-5, err.max().item()
+            else:                                   # one bf16 rounding of a value that is within 1e-5
+                assert bool((err <= 2.0 ** -8 * want.abs() + 1e-5).all()), err.max().item()
+            assert (out_lse - want_lse).abs().max().item() <= 1e-5
+        # O rows of shards that feed a final row are left alone, the others are as before
         assert torch.isnan(parts_o[:S][fin]).all() and torch.equal(parts_o[:S][~fin], o[~fin])
     ref_o, ref_lse = oracle.local_partials(b)
     ref_m, ref_mlse = oracle.merge_requests(np.concatenate([ref_o, rem_o]), np.concatenate([ref_lse, rem_lse]),
