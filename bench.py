@@ -76,6 +76,13 @@ def main():
     ap.add_argument("--merge-all", action="store_true",
                     help="every output row goes through nanocp_merge_partials (default: requests whose only partial "
                          "is a local shard are written in final form by the attention kernel itself)")
+    ap.add_argument("--graph", action="store_true",
+                    help="bucket mode: the step is recorded once as a HIP graph over a plan image; every timed step "
+                         "re-injects the image (pack + asynchronous copy) and replays the graph")
+    ap.add_argument("--image-eager", action="store_true",
+                    help="with --graph: do not record a graph, launch the image-driven step eagerly every time")
+    ap.add_argument("--inject-once", action="store_true",
+                    help="with --graph: inject the plan image once instead of before every step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-straggle", action="store_true")
     ap.add_argument("--dump-tiles", default="", help="write the tile list and per-tile device clocks to this .npz")
@@ -150,6 +157,92 @@ def main():
             nanocp.nanocp_merge_partials(db.desc, parts_o, parts_lse, rest_offsets, rest_index, n_rest, out,
                                          out_rows=rest_rows)
 
+    graph_info = {}
+    if args.graph:
+        if args.merge_all:
+            print("--graph uses the final-row path; drop --merge-all", file=sys.stderr)
+            sys.exit(2)
+        nt = db.plan.num_tiles
+        bucket = nanocp.Bucket(nt + nt // 4 + 64, db.plan.num_chunks + db.plan.num_chunks // 4 + 64,
+                               nt + 64 + d.num_kv_heads * S, nt + 64)
+        img_bytes = nanocp.bucket_plan_bytes(bucket)
+        # two images: while the step of one parity runs, the image of the other is injected on a copy stream
+        host_imgs = [torch.empty(img_bytes, dtype=torch.uint8).pin_memory() for _ in range(2)]
+        dev_imgs = [torch.zeros(img_bytes, dtype=torch.uint8, device="cuda") for _ in range(2)]
+        host_img = host_imgs[0]
+        ws_b = torch.empty(max(nanocp.bucket_workspace_bytes(db.desc, bucket), 16), dtype=torch.uint8, device="cuda")
+        m_count = torch.tensor([n_rest], dtype=torch.int32, device="cuda")
+        m_offs = torch.zeros(R + 1, dtype=torch.int32, device="cuda")
+        m_idx = torch.zeros(max(len(db.rest_index), 1), dtype=torch.int32, device="cuda")
+        m_rows = torch.zeros(R, dtype=torch.int32, device="cuda")
+        m_offs[: len(db.rest_offsets)] = rest_offsets
+        m_idx[: len(db.rest_index)] = rest_index
+        m_rows[:n_rest] = rest_rows
+        mb = batch.block_table.shape[1]
+        # host side of an iteration whose batch composition changed: new plan, final rows, image
+        t_h = time.perf_counter()
+        reps = 20
+        for _ in range(reps):
+            pl = nanocp.Plan(db.desc, batch.shards, batch.q.shape[0], batch.block_table.shape[0], mb, args.tile_tokens)
+            pl.set_final_rows(db.shard_final_row, R)
+            pl.pack(bucket, host_img)
+            pl.close()
+        graph_info["host_us_plan_create_and_pack"] = (time.perf_counter() - t_h) / reps * 1e6
+        t_h = time.perf_counter()
+        for _ in range(200):
+            db.plan.pack(bucket, host_img)
+        graph_info["host_us_pack"] = (time.perf_counter() - t_h) / 200 * 1e6
+        graph_info["image_bytes"] = img_bytes
+
+        def gstep(i):
+            k, v, ks, vs = pools[i & 1]
+            nanocp.nanocp_decode_attn_partial_image(db.desc, bucket, dev_imgs[i & 1], 0, mb, db.q, k, v, ks, vs,
+                                                    db.block_table, local_o, local_lse, ws_b, final_out=out)
+            nanocp.nanocp_merge_partials_dyn(db.desc, parts_o, parts_lse, m_offs, m_idx, R, m_count, m_rows, out)
+
+        for par in (0, 1):
+            db.plan.pack(bucket, host_imgs[par])
+            dev_imgs[par].copy_(host_imgs[par], non_blocking=True)
+        gstep(0)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        copy_stream = torch.cuda.Stream()
+        done_ev = [torch.cuda.Event(), torch.cuda.Event()]
+        copied_ev = [torch.cuda.Event(), torch.cuda.Event()]
+        for e in done_ev:
+            e.record()
+        graphs = []
+        for par in (0, 1):                       # one graph per KV pool copy (the pools alternate to defeat the cache)
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                gstep(par)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                gstep(par)
+            graphs.append(g)
+        eager_step = step
+
+        def step(i, ev=None):                    # noqa: F811  (replaces the eager step in the timed loops below)
+            par = i & 1
+            if not args.inject_once:
+                done_ev[par].synchronize()        # the step that last used this image (two steps back) has finished
+                db.plan.pack(bucket, host_imgs[par])
+                with torch.cuda.stream(copy_stream):
+                    dev_imgs[par].copy_(host_imgs[par], non_blocking=True)
+                    copied_ev[par].record()
+                torch.cuda.current_stream().wait_event(copied_ev[par])
+            if ev:
+                ev[0].record()
+            if args.image_eager:
+                gstep(i)
+            else:
+                graphs[par].replay()
+            if ev:
+                ev[1].record()
+            done_ev[par].record()
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -213,7 +306,9 @@ def main():
                    "requests": R, "local_kv_tokens": batch.local_tokens, "kv_bytes": kv_bytes,
                    "remote_partials": int(n_rem), "kernel": db.plan.kernel,
                    "rows_final_from_kernel": 0 if args.merge_all else int(len(set(db.shard_final_row[db.shard_final_row >= 0].tolist()))),
-                   "rows_merged": int(R) if args.merge_all else int(n_rest), "us_per_step": ms_per_step * 1e3,
+                   "rows_merged": int(R) if args.merge_all else int(n_rest),
+                   "mode": "graph replay over a plan image, re-injected every step" if args.graph else "eager launches",
+                   **graph_info, "us_per_step": ms_per_step * 1e3,
                    "pct_of_hbm_peak": 100.0 * kv_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, **extra},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

@@ -203,6 +203,43 @@ nanocp_status nanocp_merge_partials_rows(const nanocp_attn_desc* desc, const flo
                                          const int32_t* out_rows, void* out, int32_t out_dtype, float* out_lse,
                                          void* stream);
 
+/*
+ * Buckets: launches that can be recorded once and replayed for any batch composition (paper: AOT Graph Engine --
+ * pre-allocated pools sized by a bucket's capacities, control metadata injected by asynchronous copies before the
+ * replay, no allocation and no host decision on the replay path).
+ * A bucket fixes capacities; nanocp_plan_pack serialises a plan that fits them into a HOST image of
+ * nanocp_bucket_plan_bytes bytes whose layout depends on the bucket only.  The caller copies the image to a DEVICE
+ * buffer of the same size (256-byte aligned; any stream-ordered copy) and runs nanocp_decode_attn_partial_image,
+ * which takes the batch shape from the image on the device: the same call, with the same arguments, is valid for
+ * every image of the bucket, so it can be captured in a HIP graph together with nanocp_merge_partials_dyn (the
+ * row-indexed merge over at most max_out lists, the actual count read from *num_out_dev on the device).
+ * num_cus workgroups are launched whatever the batch is (0 = query the current device).  final_out may be NULL.
+ * One image must not be in use by two launches at a time (it holds the work-queue counters).
+ * Errors: EBOUNDS if the plan exceeds the bucket or a buffer is too small; otherwise as the calls they mirror.
+ */
+typedef struct {
+  int32_t max_tiles;   /* tiles of the work-list */
+  int32_t max_chunks;  /* work-queue entries */
+  int32_t max_segs;    /* (shard, head) results made of several tiles, and empty shards x heads */
+  int32_t max_slots;   /* tile partials held in the workspace */
+} nanocp_bucket;
+
+size_t nanocp_bucket_plan_bytes(const nanocp_bucket* bucket);
+size_t nanocp_bucket_workspace_bytes(const nanocp_attn_desc* desc, const nanocp_bucket* bucket);
+nanocp_status nanocp_plan_pack(const nanocp_plan* plan, const nanocp_bucket* bucket, void* host_image,
+                               size_t image_bytes);
+nanocp_status nanocp_decode_attn_partial_image(const nanocp_attn_desc* desc, const nanocp_bucket* bucket,
+                                               const void* device_image, int32_t num_cus, int32_t max_blocks_per_row,
+                                               const void* q, const void* k_pool, const void* v_pool,
+                                               const float* k_scale, const float* v_scale,
+                                               const int32_t* block_table, float* out_o, float* out_lse,
+                                               void* workspace, size_t workspace_bytes, void* final_out,
+                                               int32_t final_dtype, float* final_lse, void* stream);
+nanocp_status nanocp_merge_partials_dyn(const nanocp_attn_desc* desc, const float* o_parts, const float* lse_parts,
+                                        const int32_t* part_offsets, const int32_t* part_index, int32_t max_out,
+                                        const int32_t* num_out_dev, const int32_t* out_rows, void* out,
+                                        int32_t out_dtype, float* out_lse, void* stream);
+
 const char* nanocp_status_str(nanocp_status s);
 
 #ifdef __cplusplus

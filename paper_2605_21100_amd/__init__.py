@@ -43,7 +43,15 @@ TILE_DTYPE = np.dtype([(n, np.int32) for n, _ in Tile._fields_])
 EXPORTS = ["nanocp_plan_create", "nanocp_plan_query", "nanocp_plan_tiles", "nanocp_plan_kernel",
            "nanocp_plan_upload", "nanocp_plan_destroy", "nanocp_decode_attn_partial",
            "nanocp_decode_attn_partial_timed", "nanocp_merge_partials", "nanocp_status_str",
-           "nanocp_plan_set_final_rows", "nanocp_decode_attn_partial_final", "nanocp_merge_partials_rows"]
+           "nanocp_plan_set_final_rows", "nanocp_decode_attn_partial_final", "nanocp_merge_partials_rows",
+           "nanocp_bucket_plan_bytes", "nanocp_bucket_workspace_bytes", "nanocp_plan_pack",
+           "nanocp_decode_attn_partial_image", "nanocp_merge_partials_dyn"]
+
+
+class Bucket(ctypes.Structure):
+    """Capacities of a bucket of batch compositions (see include/nanocp.h)."""
+    _fields_ = [("max_tiles", ctypes.c_int32), ("max_chunks", ctypes.c_int32), ("max_segs", ctypes.c_int32),
+                ("max_slots", ctypes.c_int32)]
 
 
 
@@ -70,6 +78,14 @@ def _load():
     lib.nanocp_plan_set_final_rows.argtypes = [vp, vp, i32]
     lib.nanocp_decode_attn_partial_final.argtypes = [vp] * 9 + [vp, sz, vp, i32, vp, vp]
     lib.nanocp_merge_partials_rows.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, i32, vp, vp, i32, vp, vp]
+    lib.nanocp_bucket_plan_bytes.argtypes = [ctypes.POINTER(Bucket)]
+    lib.nanocp_bucket_plan_bytes.restype = sz
+    lib.nanocp_bucket_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(Bucket)]
+    lib.nanocp_bucket_workspace_bytes.restype = sz
+    lib.nanocp_plan_pack.argtypes = [vp, ctypes.POINTER(Bucket), vp, sz]
+    lib.nanocp_decode_attn_partial_image.argtypes = ([ctypes.POINTER(AttnDesc), ctypes.POINTER(Bucket), vp, i32, i32] +
+                                                     [vp] * 8 + [vp, sz, vp, i32, vp, vp])
+    lib.nanocp_merge_partials_dyn.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, i32, vp, vp, vp, i32, vp, vp]
     lib.nanocp_status_str.argtypes = [ctypes.c_int]
     lib.nanocp_status_str.restype = ctypes.c_char_p
     return lib
@@ -152,6 +168,12 @@ class Plan:
         self._query()       # the partial slots (workspace size) were re-derived
         return self
 
+    def pack(self, bucket, host_image):
+        """Serialise into host_image (a pinned uint8 torch tensor or numpy array of bucket_plan_bytes(bucket))."""
+        ptr = host_image.data_ptr() if hasattr(host_image, "data_ptr") else host_image.ctypes.data
+        nbytes = host_image.numel() if hasattr(host_image, "numel") else host_image.nbytes
+        _check(_lib.nanocp_plan_pack(self._h, ctypes.byref(bucket), ctypes.c_void_p(ptr), nbytes), "nanocp_plan_pack")
+
     def upload(self, stream=None):
         _check(_lib.nanocp_plan_upload(self._h, _stream(stream)), "nanocp_plan_upload")
         self.uploaded = True
@@ -211,6 +233,38 @@ def nanocp_merge_partials(desc, o_parts, lse_parts, part_offsets, part_index, nu
         _check(_lib.nanocp_merge_partials_rows(ctypes.byref(desc), _ptr(o_parts), _ptr(lse_parts), _ptr(part_offsets),
                                                _ptr(part_index), num_out, _ptr(out_rows), _ptr(out), out_dtype,
                                                _ptr(out_lse), _stream(stream)), "nanocp_merge_partials_rows")
+
+
+def bucket_plan_bytes(bucket):
+    return int(_lib.nanocp_bucket_plan_bytes(ctypes.byref(bucket)))
+
+
+def bucket_workspace_bytes(desc, bucket):
+    return int(_lib.nanocp_bucket_workspace_bytes(ctypes.byref(desc), ctypes.byref(bucket)))
+
+
+def nanocp_decode_attn_partial_image(desc, bucket, image, num_cus, max_blocks_per_row, q, k_pool, v_pool, k_scale,
+                                     v_scale, block_table, out_o, out_lse, workspace, final_out=None, final_lse=None,
+                                     stream=None):
+    """Phase 2 driven by a plan image on the device (same call for every plan of the bucket: graph-capturable)."""
+    import torch
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    fdt = BF16 if (final_out is not None and final_out.dtype == torch.bfloat16) else F32
+    _check(_lib.nanocp_decode_attn_partial_image(ctypes.byref(desc), ctypes.byref(bucket), _ptr(image), num_cus,
+                                                 max_blocks_per_row, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(k_scale),
+                                                 _ptr(v_scale), _ptr(block_table), _ptr(out_o), _ptr(out_lse),
+                                                 _ptr(workspace), ws_bytes, _ptr(final_out), fdt, _ptr(final_lse),
+                                                 _stream(stream)), "nanocp_decode_attn_partial_image")
+
+
+def nanocp_merge_partials_dyn(desc, o_parts, lse_parts, part_offsets, part_index, max_out, num_out_dev, out_rows, out,
+                              out_lse=None, stream=None):
+    """Row-indexed merge over at most max_out lists; the count is read from num_out_dev (int32 [1]) on the device."""
+    import torch
+    out_dtype = BF16 if out.dtype == torch.bfloat16 else F32
+    _check(_lib.nanocp_merge_partials_dyn(ctypes.byref(desc), _ptr(o_parts), _ptr(lse_parts), _ptr(part_offsets),
+                                          _ptr(part_index), max_out, _ptr(num_out_dev), _ptr(out_rows), _ptr(out),
+                                          out_dtype, _ptr(out_lse), _stream(stream)), "nanocp_merge_partials_dyn")
 
 
 def split_final_rows(part_offsets, part_index, num_local, single_only=False):

@@ -28,8 +28,10 @@ __global__ __launch_bounds__(kThreads) void reduce_tiles_kernel(const Seg* __res
                                                                 const float* __restrict__ ws_lse,
                                                                 float* __restrict__ out_o, float* __restrict__ out_lse,
                                                                 void* __restrict__ final_out,
-                                                                float* __restrict__ final_lse, int final_bf16, int Hq,
-                                                                int G, int Dv) {
+                                                                float* __restrict__ final_lse, int final_bf16,
+                                                                const int32_t* __restrict__ header, int Hq, int G,
+                                                                int Dv) {
+  if (header && (int)blockIdx.x >= header[1]) return;  // plan image: launched for the bucket's capacity
   const Seg sg = segs[blockIdx.x];
   const int q4 = Dv >> 2;
   const int i4 = blockIdx.y * kThreads + threadIdx.x;
@@ -99,8 +101,10 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float* __restrict
                                                          const float* __restrict__ lse_parts,
                                                          const int32_t* __restrict__ part_offsets,
                                                          const int32_t* __restrict__ part_index,
-                                                         const int32_t* __restrict__ out_rows, void* __restrict__ out,
+                                                         const int32_t* __restrict__ out_rows,
+                                                         const int32_t* __restrict__ num_out_dev, void* __restrict__ out,
                                                          float* __restrict__ out_lse, int Hq, int Dv) {
+  if (num_out_dev && (int)blockIdx.x >= *num_out_dev) return;  // launched for a capacity, the count is on the device
   const int b = part_offsets[blockIdx.x], e = part_offsets[blockIdx.x + 1];
   const int r = out_rows ? out_rows[blockIdx.x] : (int)blockIdx.x;  // output row of this list
   const int q4 = Dv >> 2;  // float4 groups per head (Dv % 4 == 0 is checked by the host)
@@ -183,6 +187,29 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float* __restrict
   if (out_lse && (i4 % q4) == 0) out_lse[(size_t)r * Hq + a] = lse;
 }
 
+// the tile kernel of the variant, then the reduction kernel over `num_segs` segments (0 = none)
+nanocp_status launch_tiles_and_reduce(const nanocp_attn_desc& d, int variant, const KParams& p, int blocks,
+                                      const Seg* d_segs, int num_segs, hipStream_t st) {
+  if (blocks > 0) {
+    hipError_t e;
+    if (variant == kGeneric)
+      e = launch_generic(d, p, blocks, st);
+    else if (variant == kMlaMfmaBf16)
+      e = launch_mla_mfma(p, blocks, st);
+    else
+      e = launch_gqa_mfma(variant, p, blocks, st);
+    if (e != hipSuccess) return NANOCP_EHIP;
+  }
+  if (num_segs > 0) {
+    if (p.Dv % 4) return NANOCP_ESHAPE;
+    const unsigned per_seg = (unsigned)((p.G * (p.Dv / 4) + kThreads - 1) / kThreads);
+    hipLaunchKernelGGL(reduce_tiles_kernel, dim3((unsigned)num_segs, per_seg), dim3(kThreads), 0, st, d_segs, p.ws_o,
+                       p.ws_lse, p.out_o, p.out_lse, p.final_out, p.final_lse, p.final_bf16, p.header, p.Hq, p.G, p.Dv);
+    if (hipGetLastError() != hipSuccess) return NANOCP_EHIP;
+  }
+  return NANOCP_OK;
+}
+
 nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_pool, const void* v_pool,
                           const float* k_scale, const float* v_scale, const int32_t* block_table, float* out_o,
                           float* out_lse, void* workspace, size_t workspace_bytes, uint64_t* tile_clock, void* final_out,
@@ -226,6 +253,7 @@ nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_
   p.chunk_offsets = plan->d_chunk_offsets;
   p.sync = plan->d_sync;
   p.num_chunks = plan->num_chunks;
+  p.header = nullptr;
   p.tile_clock = tile_clock;
   p.final_out = final_out;
   p.final_lse = final_out ? final_lse : nullptr;
@@ -240,25 +268,8 @@ nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_
   p.kind = d.kind;
   p.scale = d.softmax_scale;
 
-  if (plan->num_chunks > 0) {
-    hipError_t e;
-    if (plan->variant == kGeneric)
-      e = launch_generic(d, p, plan->launch_blocks, st);
-    else if (plan->variant == kMlaMfmaBf16)
-      e = launch_mla_mfma(p, plan->launch_blocks, st);
-    else
-      e = launch_gqa_mfma(plan->variant, p, plan->launch_blocks, st);
-    if (e != hipSuccess) return NANOCP_EHIP;
-  }
-  if (!plan->segs.empty()) {
-    if (p.Dv % 4) return NANOCP_ESHAPE;
-    const unsigned per_seg = (unsigned)((G * (p.Dv / 4) + kThreads - 1) / kThreads);
-    hipLaunchKernelGGL(reduce_tiles_kernel, dim3((unsigned)plan->segs.size(), per_seg), dim3(kThreads), 0, st,
-                       plan->d_segs, p.ws_o, p.ws_lse, out_o, out_lse, p.final_out, p.final_lse, p.final_bf16, p.Hq, G,
-                       p.Dv);
-    if (hipGetLastError() != hipSuccess) return NANOCP_EHIP;
-  }
-  return NANOCP_OK;
+  return launch_tiles_and_reduce(d, plan->variant, p, plan->num_chunks > 0 ? plan->launch_blocks : 0, plan->d_segs,
+                                 (int)plan->segs.size(), st);
 }
 
 }  // namespace
@@ -284,6 +295,75 @@ nanocp_status nanocp_decode_attn_partial_final(const nanocp_plan* plan, const vo
                              workspace_bytes, nullptr, final_out, final_dtype, final_lse, stream);
 }
 
+nanocp_status nanocp_decode_attn_partial_image(const nanocp_attn_desc* desc, const nanocp_bucket* bucket,
+                                               const void* device_image, int32_t num_cus, int32_t max_blocks_per_row,
+                                               const void* q, const void* k_pool, const void* v_pool,
+                                               const float* k_scale, const float* v_scale,
+                                               const int32_t* block_table, float* out_o, float* out_lse,
+                                               void* workspace, size_t workspace_bytes, void* final_out,
+                                               int32_t final_dtype, float* final_lse, void* stream) {
+  using namespace nanocp;
+  if (!desc || !bucket || !device_image || num_cus < 0 || max_blocks_per_row < 0) return NANOCP_EINVAL;
+  if (bucket->max_tiles < 0 || bucket->max_chunks < 0 || bucket->max_segs < 0 || bucket->max_slots < 0)
+    return NANOCP_EINVAL;
+  const nanocp_attn_desc& d = *desc;
+  if (d.num_q_heads <= 0 || d.num_kv_heads <= 0 || d.num_q_heads % d.num_kv_heads) return NANOCP_ESHAPE;
+  if (!q || !k_pool || !block_table || !out_o || !out_lse) return NANOCP_EINVAL;
+  if (d.kind == NANOCP_GQA && !v_pool) return NANOCP_EINVAL;
+  if (d.kv_dtype == NANOCP_FP8_E4M3 && (!k_scale || !v_scale)) return NANOCP_EINVAL;
+  if (final_out && final_dtype != NANOCP_F32 && final_dtype != NANOCP_BF16) return NANOCP_EUNSUPPORTED;
+  if (final_out && d.head_dim_v % 8) return NANOCP_ESHAPE;
+  const size_t ws_need = nanocp_bucket_workspace_bytes(desc, bucket);
+  if (ws_need > 0 && (!workspace || workspace_bytes < ws_need)) return NANOCP_EBOUNDS;
+  if (((uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)workspace | (uintptr_t)out_o |
+       (uintptr_t)final_out) & 15)
+    return NANOCP_EINVAL;
+  if ((uintptr_t)device_image & 255) return NANOCP_EINVAL;
+  if (num_cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return NANOCP_EHIP;
+    num_cus = prop.multiProcessorCount;
+  }
+  const int variant = pick_variant(d);
+  const ImageLayout L = image_layout(*bucket);
+  const char* img = (const char*)device_image;
+  const int G = d.num_q_heads / d.num_kv_heads;
+  KParams p;
+  p.q = q;
+  p.k_pool = k_pool;
+  p.v_pool = v_pool;
+  p.k_scale = k_scale;
+  p.v_scale = v_scale;
+  p.block_table = block_table;
+  p.out_o = out_o;
+  p.out_lse = out_lse;
+  p.ws_o = (float*)workspace;
+  p.ws_lse = (float*)((char*)workspace + align256((size_t)bucket->max_slots * G * d.head_dim_v * sizeof(float)));
+  p.tiles = (const DevTile*)(img + L.tiles);
+  p.chunk_offsets = (const int32_t*)(img + L.chunk_offsets);
+  p.sync = (int32_t*)(img + L.sync);
+  p.num_chunks = 0;
+  p.header = (const int32_t*)(img + L.header);
+  p.tile_clock = nullptr;
+  p.final_out = final_out;
+  p.final_lse = final_out ? final_lse : nullptr;
+  p.final_bf16 = final_dtype == NANOCP_BF16;
+  p.Hq = d.num_q_heads;
+  p.Hkv = d.num_kv_heads;
+  p.G = G;
+  p.Dk = d.head_dim_qk;
+  p.Dv = d.head_dim_v;
+  p.ps = d.page_size;
+  p.max_blocks = max_blocks_per_row;
+  p.kind = d.kind;
+  p.scale = d.softmax_scale;
+  // dynamic variants: one workgroup per compute unit pulls chunks; the generic kernel runs one workgroup per chunk
+  const int blocks = variant == kGeneric ? bucket->max_chunks : num_cus;
+  return launch_tiles_and_reduce(d, variant, p, blocks, (const Seg*)(img + L.segs), bucket->max_segs,
+                                 (hipStream_t)stream);
+}
+
 nanocp_status nanocp_decode_attn_partial_timed(const nanocp_plan* plan, const void* q, const void* k_pool,
                                                const void* v_pool, const float* k_scale, const float* v_scale,
                                                const int32_t* block_table, float* out_o, float* out_lse,
@@ -305,6 +385,14 @@ nanocp_status nanocp_merge_partials_rows(const nanocp_attn_desc* desc, const flo
                                          const int32_t* part_offsets, const int32_t* part_index, int32_t num_out,
                                          const int32_t* out_rows, void* out, int32_t out_dtype, float* out_lse,
                                          void* stream) {
+  return nanocp_merge_partials_dyn(desc, o_parts, lse_parts, part_offsets, part_index, num_out, nullptr, out_rows, out,
+                                   out_dtype, out_lse, stream);
+}
+
+nanocp_status nanocp_merge_partials_dyn(const nanocp_attn_desc* desc, const float* o_parts, const float* lse_parts,
+                                        const int32_t* part_offsets, const int32_t* part_index, int32_t num_out,
+                                        const int32_t* num_out_dev, const int32_t* out_rows, void* out,
+                                        int32_t out_dtype, float* out_lse, void* stream) {
   if (!desc || num_out < 0) return NANOCP_EINVAL;
   if (desc->num_q_heads <= 0 || desc->head_dim_v <= 0) return NANOCP_EINVAL;
   if (out_dtype != NANOCP_F32 && out_dtype != NANOCP_BF16) return NANOCP_EUNSUPPORTED;
@@ -318,10 +406,10 @@ nanocp_status nanocp_merge_partials_rows(const nanocp_attn_desc* desc, const flo
   hipStream_t st = (hipStream_t)stream;
   if (out_dtype == NANOCP_BF16)
     hipLaunchKernelGGL((nanocp::merge_kernel<true>), grid, dim3(nanocp::kThreads), 0, st, o_parts, lse_parts,
-                       part_offsets, part_index, out_rows, out, out_lse, Hq, Dv);
+                       part_offsets, part_index, out_rows, num_out_dev, out, out_lse, Hq, Dv);
   else
     hipLaunchKernelGGL((nanocp::merge_kernel<false>), grid, dim3(nanocp::kThreads), 0, st, o_parts, lse_parts,
-                       part_offsets, part_index, out_rows, out, out_lse, Hq, Dv);
+                       part_offsets, part_index, out_rows, num_out_dev, out, out_lse, Hq, Dv);
   return hipGetLastError() == hipSuccess ? NANOCP_OK : NANOCP_EHIP;
 }
 

@@ -51,6 +51,7 @@ __global__ __launch_bounds__(kThreads) void generic_partial_kernel(KParams p) {
   const bool fp8 = sizeof(KT) == 1;
   const int Dk = p.Dk, Dv = p.Dv, ps = p.ps, Hkv = p.Hkv, G = p.G;
 
+  if (p.header && (int)blockIdx.x >= p.header[0]) return;  // plan image: launched for the bucket's capacity
   const int t0 = p.chunk_offsets[blockIdx.x], t1 = p.chunk_offsets[blockIdx.x + 1];
   for (int ti = t0; ti < t1; ++ti) {
     const DevTile tile = p.tiles[ti];

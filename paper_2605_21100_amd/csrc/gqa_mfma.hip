@@ -167,16 +167,24 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
   // ordered from large to small chunks, so differences in speed between workgroups even out at the end.
   const cptr<int32_t> chunk_offsets = as_const(p.chunk_offsets);
   const cptr<int32_t> tile_words = as_const((const int32_t*)p.tiles);
-  for (int chunk = blockIdx.x; chunk < p.num_chunks;) {
+  auto load_tile = [&](int ti) {
+    DevTile t;
+    const cptr<int32_t> w = tile_words + (size_t)ti * (sizeof(DevTile) / 4);
+    t.q_row = w[0], t.bt_row = w[1], t.kv_head = w[2], t.shard = w[3];
+    t.tok_begin = w[4], t.tok_end = w[5], t.dst = w[6], t.seg = w[7];
+    t.n_parts = w[8], t.slot_begin = w[9], t.final_row = w[10];
+    return t;
+  };
+  const int num_chunks = p.header ? as_const(p.header)[0] : p.num_chunks;  // plan image: the count lives on the device
+  for (int chunk = blockIdx.x; chunk < num_chunks;) {
   const int t0 = chunk_offsets[chunk], t1 = chunk_offsets[chunk + 1];
+  DevTile tile_next = load_tile(t0);
   for (int ti = t0; ti < t1; ++ti) {
-    DevTile tile;
-    {
-      const cptr<int32_t> w = tile_words + (size_t)ti * (sizeof(DevTile) / 4);
-      tile.q_row = w[0], tile.bt_row = w[1], tile.kv_head = w[2], tile.shard = w[3];
-      tile.tok_begin = w[4], tile.tok_end = w[5], tile.dst = w[6], tile.seg = w[7];
-      tile.n_parts = w[8], tile.slot_begin = w[9], tile.final_row = w[10];
-    }
+    const DevTile tile = tile_next;
+    // the next tile's record is fetched now (scalar loads), so that its latency is not on the next tile's critical
+    // path in front of the block-table and K/V loads; reading one record past the chunk is harmless only inside
+    // the list, hence the clamp
+    tile_next = load_tile(ti + 1 < t1 ? ti + 1 : ti);
     uint64_t clk0 = 0;
     if (p.tile_clock && tid == 0) clk0 = wall_clock64();
     const int h = tile.kv_head;
@@ -363,7 +371,11 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
     // software pipeline over the full steps: the loads of step n+1 are in flight while step n is
     // computed, and the block-table entry of step n+2 is fetched one step ahead.  The steady state has
     // no conditional loads, so the wait for the older buffer is a counted one, not a drain.
-    StepRegs<kFp8> ra, rb;
+    StepRegs<kFp8> ra, rb, rc;
+    // the ragged step of this wavefront (the head by the last wavefront, the tail by the one before it) is
+    // requested first and computed last: its latency hides behind the full steps
+    const int ru = wave == kWaves - 1 ? rag0 : (wave == kWaves - 2 ? rag1 : -1);
+    if (ru >= 0) load_step(rc, ru, page_of(ru));
     if (u < u_end) {
       load_step(ra, u, page_of(u));
       int pg_next = page_of(u + kWaves);
@@ -386,14 +398,7 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
         u += kWaves;
       }
     }
-    // ragged steps: the head by the last wavefront, the tail by the one before it
-    {
-      const int ru = wave == kWaves - 1 ? rag0 : (wave == kWaves - 2 ? rag1 : -1);
-      if (ru >= 0) {
-        load_step(ra, ru, page_of(ru));
-        compute_step(ra, ru, std::true_type{});
-      }
-    }
+    if (ru >= 0) compute_step(rc, ru, std::true_type{});
 
     // ---- combine the 4 wavefronts' partials
     l_run = xor_sum(l_run);

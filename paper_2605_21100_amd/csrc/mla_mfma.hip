@@ -162,7 +162,8 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
   }
   const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
 
-  for (int chunk = blockIdx.x; chunk < p.num_chunks;) {
+  const int num_chunks = p.header ? as_const(p.header)[0] : p.num_chunks;  // plan image: the count lives on the device
+  for (int chunk = blockIdx.x; chunk < num_chunks;) {
     const int t0 = chunk_offsets[chunk], t1 = chunk_offsets[chunk + 1];
     for (int ti = t0; ti < t1; ++ti) {
       DevTile tile;

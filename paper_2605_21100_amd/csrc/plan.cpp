@@ -9,6 +9,7 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <cstring>
 #include <new>
 
 #include "plan.h"
@@ -42,7 +43,9 @@ nanocp_status check_desc(const nanocp_attn_desc& d) {
   return NANOCP_OK;
 }
 
-int pick_variant(const nanocp_attn_desc& d) {
+}  // namespace
+
+int nanocp::pick_variant(const nanocp_attn_desc& d) {
   const int G = d.num_q_heads / d.num_kv_heads;
   if (d.kind == NANOCP_GQA && d.q_dtype == NANOCP_BF16 && G == 16 && d.head_dim_qk == 128 && d.head_dim_v == 128) {
     if (d.kv_dtype == NANOCP_BF16 && d.page_size == 64) return kGqaMfmaBf16;
@@ -53,6 +56,8 @@ int pick_variant(const nanocp_attn_desc& d) {
     return kMlaMfmaBf16;
   return kGeneric;
 }
+
+namespace {
 
 // Planner tuning knobs can be overridden from the environment (integers, clamped).
 int env_int(const char* name, int dflt, int lo, int hi) {
@@ -159,7 +164,7 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
     p->num_q_rows = num_q_rows;
     p->num_bt_rows = num_bt_rows;
     p->max_blocks = max_blocks_per_row;
-    p->variant = pick_variant(*desc);
+    p->variant = nanocp::pick_variant(*desc);
     const int Hkv = desc->num_kv_heads;
     const int G = desc->num_q_heads / Hkv;
     p->dynamic = p->variant != kGeneric;
@@ -306,6 +311,42 @@ nanocp_status nanocp_plan_set_final_rows(nanocp_plan* plan, const int32_t* shard
     return NANOCP_ENOMEM;
   }
   plan->num_final_rows = num_out;
+  return NANOCP_OK;
+}
+
+size_t nanocp_bucket_plan_bytes(const nanocp_bucket* b) {
+  if (!b || b->max_tiles < 0 || b->max_chunks < 0 || b->max_segs < 0 || b->max_slots < 0) return 0;
+  return nanocp::image_layout(*b).total;
+}
+
+size_t nanocp_bucket_workspace_bytes(const nanocp_attn_desc* desc, const nanocp_bucket* b) {
+  if (!desc || !b || desc->num_kv_heads <= 0 || b->max_slots <= 0) return 0;
+  const size_t G = (size_t)(desc->num_q_heads / desc->num_kv_heads);
+  return nanocp::align256((size_t)b->max_slots * G * desc->head_dim_v * sizeof(float)) +
+         nanocp::align256((size_t)b->max_slots * G * sizeof(float));
+}
+
+nanocp_status nanocp_plan_pack(const nanocp_plan* plan, const nanocp_bucket* b, void* host_image, size_t image_bytes) {
+  if (!plan || !b || !host_image) return NANOCP_EINVAL;
+  if (b->max_tiles < 0 || b->max_chunks < 0 || b->max_segs < 0 || b->max_slots < 0) return NANOCP_EINVAL;
+  const nanocp::ImageLayout L = nanocp::image_layout(*b);
+  if (image_bytes < L.total) return NANOCP_EBOUNDS;
+  if ((int64_t)plan->dev_tiles.size() > b->max_tiles || plan->num_chunks > b->max_chunks ||
+      (int64_t)plan->segs.size() > b->max_segs || plan->num_multi_segs > b->max_segs || plan->num_slots > b->max_slots)
+    return NANOCP_EBOUNDS;
+  char* img = (char*)host_image;
+  std::memset(img, 0, L.chunk_offsets);  // header and counters
+  int32_t* hdr = (int32_t*)(img + L.header);
+  hdr[0] = plan->num_chunks;
+  hdr[1] = (int32_t)plan->segs.size();
+  hdr[2] = plan->num_multi_segs;
+  hdr[3] = plan->num_slots;
+  hdr[4] = plan->variant;
+  hdr[5] = plan->grouped ? 1 : 0;
+  hdr[6] = plan->num_final_rows;
+  std::memcpy(img + L.chunk_offsets, plan->chunk_offsets.data(), plan->chunk_offsets.size() * sizeof(int32_t));
+  std::memcpy(img + L.tiles, plan->dev_tiles.data(), plan->dev_tiles.size() * sizeof(nanocp::DevTile));
+  std::memcpy(img + L.segs, plan->segs.data(), plan->segs.size() * sizeof(nanocp::Seg));
   return NANOCP_OK;
 }
 

@@ -8,6 +8,7 @@
 namespace nanocp {
 
 enum Variant : int32_t { kGeneric = 0, kGqaMfmaBf16 = 1, kGqaMfmaFp8 = 2, kMlaMfmaBf16 = 3 };
+int pick_variant(const nanocp_attn_desc& d);  // which tile kernel handles this problem shape
 
 // Reduction segment: the tile partials of one (shard, kv head).  Only segments with
 // n_parts != 1 exist (0 parts = empty shard, filled with O = 0 / LSE = -inf).
@@ -53,13 +54,33 @@ struct KParams {
   const int32_t* chunk_offsets;
   int32_t* sync;         // plan-owned counters (see kSyncSegBase)
   int32_t num_chunks;
-  uint64_t* tile_clock;  // may be null
+  const int32_t* header;  // null, or the counts on the device (plan image): they then override num_chunks
+  uint64_t* tile_clock;   // may be null
   void* final_out;       // [num_out, Hq, Dv] float or bf16; null = every shard writes out_o / out_lse
   float* final_lse;      // [num_out, Hq], may be null
   int32_t final_bf16;
   int32_t Hq, Hkv, G, Dk, Dv, ps, max_blocks, kind;
   float scale;
 };
+
+// Plan image: the device-side part of a plan as one relocatable block whose layout depends only on the bucket's
+// capacities, so that launches recorded once (HIP graph) serve every plan that fits the bucket.
+// header words: [0] chunks, [1] reduction segments (separate kernel), [2] fused segments, [3] partial slots
+constexpr int kHeaderWords = 64;
+struct ImageLayout {
+  size_t header, sync, chunk_offsets, tiles, segs, total;
+};
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline ImageLayout image_layout(const nanocp_bucket& b) {
+  ImageLayout L;
+  L.header = 0;
+  L.sync = align256(kHeaderWords * sizeof(int32_t));
+  L.chunk_offsets = L.sync + align256((size_t)(kSyncSegBase + b.max_segs) * sizeof(int32_t));
+  L.tiles = L.chunk_offsets + align256((size_t)(b.max_chunks + 1) * sizeof(int32_t));
+  L.segs = L.tiles + align256((size_t)b.max_tiles * sizeof(DevTile));
+  L.total = L.segs + align256((size_t)b.max_segs * sizeof(Seg));
+  return L;
+}
 
 }  // namespace nanocp
 
