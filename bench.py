@@ -24,9 +24,10 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the tile kernel, from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a 1 GiB copy
 # (summaries and commands under profiles/); valid for the default plan of the named config only.
-MEASURED_TRAFFIC_BYTES = {3: (1207934245, "profiles/gqa_mfma_bf16_config3_mixed_dcp.md"),
-                          5: (774344193, "profiles/gqa_mfma_fp8_config5_long_shard.md"),
-                          2: (659350176, "profiles/gqa_mfma_bf16_config2_local.md")}
+MEASURED_TRAFFIC_BYTES = {3: (1205877004, "profiles/gqa_mfma_bf16_config3_mixed_dcp.md"),
+                          5: (770151075, "profiles/gqa_mfma_fp8_config5_long_shard.md"),
+                          2: (658320499, "profiles/gqa_mfma_bf16_config2_local.md"),
+                          4: (1609056635, "profiles/mla_mfma_bf16_config4.md")}
 METRIC = "decode-attention KV GB/s (% of HBM peak) + µs/step, mixed ragged DCP batch"
 WORKLOAD_NAMES = {1: "config1: tiny fp32 GQA", 2: "config2: bf16 GQA 64 local requests U[1024,8192]",
                   3: "config3: mixed long-tail DCP batch, 128 requests lognormal(median 2048, sigma 1.2), bf16 GQA 64q/4kv d128",
@@ -267,13 +268,17 @@ def main():
     extra = {}
     if not args.no_straggle:
         # per tile: device clock at start / end and the workgroup that ran it (instrumented entry point)
-        clk = torch.zeros((max(db.plan.num_tiles, 1), 3), dtype=torch.int64, device="cuda")
+        # (same work-list; the instrumented entry point writes per-shard partials, so it gets a plan of its own)
+        plan_t = nanocp.Plan(db.desc, batch.shards, batch.q.shape[0], batch.block_table.shape[0],
+                             batch.block_table.shape[1], args.tile_tokens).upload()
+        ws_t = torch.empty(max(plan_t.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+        clk = torch.zeros((max(plan_t.num_tiles, 1), 3), dtype=torch.int64, device="cuda")
         for rep in range(3):
-            nanocp.nanocp_decode_attn_partial(db.plan, db.q, *[pools[rep & 1][j] for j in range(4)], db.block_table,
-                                              local_o, local_lse, db.workspace, tile_clock=clk)
+            nanocp.nanocp_decode_attn_partial(plan_t, db.q, *[pools[rep & 1][j] for j in range(4)], db.block_table,
+                                              local_o, local_lse, ws_t, tile_clock=clk)
         torch.cuda.synchronize()
         c = clk.cpu().numpy().astype(np.int64)
-        tiles = db.plan.tiles()
+        tiles = plan_t.tiles()
         if args.dump_tiles:
             np.savez(args.dump_tiles, tiles=tiles, clock=c)
         t0 = c[:, 0].min()
@@ -283,7 +288,7 @@ def main():
         np.maximum.at(finish, wg, (c[:, 1] - t0) / 100.0)            # 100 MHz clock -> microseconds
         # the first n_wg chunks of the queue have equal cost by construction: their run times are the
         # "tile times" whose spread says how much one piece of the work-list can straggle
-        nch = db.plan.num_chunks
+        nch = plan_t.num_chunks
         c_start = np.full(nch, np.iinfo(np.int64).max)
         c_end = np.zeros(nch, np.int64)
         np.minimum.at(c_start, tiles["chunk"], c[:, 0])
@@ -295,7 +300,8 @@ def main():
                  "equal_chunk_us_mean": float(head.mean()), "equal_chunk_us_max": float(head.max()),
                  "straggle_equal_chunk_max_over_mean": float(head.max() / head.mean())}
 
-    default_plan = args.tile_tokens == 0 and not any(k.startswith("NANOCP_") for k in os.environ)
+    default_plan = (args.tile_tokens == 0 and not args.merge_all and not args.graph and
+                    not any(k.startswith("NANOCP_") for k in os.environ))
     traffic, traffic_src = (MEASURED_TRAFFIC_BYTES.get(args.config, (None, None)) if default_plan else (None, None))
     result = {
         "metric": METRIC, "value": kv_bytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1,
