@@ -176,3 +176,64 @@ def test_full_size_plans_are_balanced():
         kv_pages = int(((tiles["tok_end"] - 1) // 64 - tiles["tok_begin"] // 64 + 1).sum())
         assert 2 * n_partial * 16 * 129 * 4 <= 0.05 * kv_pages * 16384, (cid, n_partial, kv_pages)
         plan.close()
+
+
+def test_final_rows_regroup_slots_on_the_host():
+    """Shards naming one output row become one reduction segment: their tiles share consecutive slots (dst),
+    single-tile rows write directly, and the workspace is re-sized."""
+    b = W.reduced(4, with_remote_kv=False)                       # every second request split in two local shards
+    plan = _plan(b, tile_tokens=256)
+    fin, r_offs, r_idx, r_rows = nanocp.split_final_rows(b.part_offsets, b.part_index, b.num_shards)
+    assert (fin >= 0).all() and len(r_rows) == 0
+    before = plan.tiles()
+    plan.set_final_rows(fin, b.num_requests)
+    after = plan.tiles()
+    assert np.array_equal(before[["shard", "kv_head", "tok_begin", "tok_end", "chunk"]],
+                          after[["shard", "kv_head", "tok_begin", "tok_end", "chunk"]])   # the work-list itself is unchanged
+    row_of = fin[after["shard"]]
+    for r in range(b.num_requests):
+        dst = np.sort(after["dst"][row_of == r])
+        if len(dst) == 1:
+            assert dst[0] == -1
+        else:
+            assert dst[0] >= 0 and np.array_equal(dst, np.arange(dst[0], dst[0] + len(dst)))
+    slots = after["dst"][after["dst"] >= 0]
+    assert len(set(slots.tolist())) == len(slots)
+    G = b.desc.num_q_heads // b.desc.num_kv_heads
+    assert plan.workspace_bytes >= len(slots) * G * (b.desc.head_dim_v + 1) * 4
+    plan.close()
+
+
+def test_plan_image_layout_and_capacity_errors():
+    """nanocp_plan_pack is host only: header counts, chunk offsets and tiles land where the bucket's layout says;
+    a plan that exceeds any capacity, or a short buffer, is refused."""
+    b = W.reduced(3, with_remote_kv=False)
+    plan = _plan(b, tile_tokens=128)
+    nt, nc = plan.num_tiles, plan.num_chunks
+    bucket = nanocp.Bucket(nt + 5, nc + 3, nt + 4 * b.num_shards, nt)
+    nbytes = nanocp.bucket_plan_bytes(bucket)
+    assert nbytes % 256 == 0 and nbytes >= 48 * (nt + 5) + 4 * (nc + 4)
+    img = np.full(nbytes, 0xAB, np.uint8)
+    plan.pack(bucket, img)
+    hdr = img[:16].view(np.int32)
+    assert hdr[0] == nc and hdr[3] == int((plan.tiles()["dst"] >= 0).sum())
+    sync_off = 256                                                # 64 header words, then the counters
+    n_sync = 2 + bucket.max_segs
+    assert not img[sync_off:sync_off + 4 * n_sync].any()          # counters start at zero
+    co_off = sync_off + (4 * n_sync + 255) // 256 * 256
+    co = img[co_off:co_off + 4 * (nc + 1)].view(np.int32)
+    assert co[0] == 0 and co[-1] == nt and np.all(np.diff(co) > 0)
+    tiles_off = co_off + (4 * (bucket.max_chunks + 1) + 255) // 256 * 256
+    rec = img[tiles_off:tiles_off + 48 * nt].view(np.int32).reshape(nt, 12)
+    t = plan.tiles()
+    assert np.array_equal(rec[:, 3], t["shard"]) and np.array_equal(rec[:, 4], t["tok_begin"])
+    assert np.array_equal(rec[:, 6], t["dst"])
+    for bad in (nanocp.Bucket(nt - 1, nc, nt, nt), nanocp.Bucket(nt, nc - 1, nt, nt), nanocp.Bucket(nt, nc, nt, hdr[3] - 1)):
+        with pytest.raises(nanocp.NanocpError) as e:
+            plan.pack(bad, img)
+        assert e.value.status == nanocp.EBOUNDS
+    with pytest.raises(nanocp.NanocpError) as e:
+        plan.pack(bucket, img[:nbytes - 256])
+    assert e.value.status == nanocp.EBOUNDS
+    assert nanocp.bucket_workspace_bytes(plan.desc, bucket) >= plan.workspace_bytes
+    plan.close()
