@@ -321,3 +321,34 @@ def test_final_rows_errors():
     assert e.value.status == nanocp.EBOUNDS
     plan.close()
     db.plan.close()
+
+
+@pytest.mark.parametrize("cid", [1, 2, 4, 5])
+def test_peaked_scores_exercise_the_running_maximum(cid):
+    """Queries scaled by 32 (exact in every input type): scores spread over hundreds of log2 units, the softmax is
+    nearly one-hot and the running maximum moves again and again inside a tile - the rescaling paths, the masked
+    tails and the LSE at large magnitude are what is checked here."""
+    _say(f"[case] peaked scores, reduced config {cid}")
+    b = W.reduced(cid)
+    if b.q.dtype == np.uint16:                                   # bf16 bits: exponent + 5
+        q = b.q.copy()
+        nz = (q & 0x7F80) != 0
+        q[nz] = q[nz] + np.uint16(5 << 7)
+        b.q = q
+    else:
+        b.q = (b.q * np.float32(32.0)).astype(np.float32)
+    for tt in (0, 128):
+        ps = b.desc.page_size
+        db = nanocp.DeviceBatch(b, tile_tokens=0 if tt == 0 else max(ps, tt // ps * ps))
+        o, lse = db.partial()
+        torch.cuda.synchronize()
+        ref_o, ref_lse = oracle.local_partials(b)
+        assert np.abs(ref_lse).max() > 20.0                      # the case really is extreme
+        if b.desc.kv_dtype == "f32":
+            # scores reach |s| ~ 100 here, where one fp32 ulp of a score is 8e-6: the 1e-5 bar of the ordinary cases
+            # is below what fp32 scores can resolve; 1e-4 = a dozen ulps of the largest score
+            assert np.abs(o.cpu().numpy() - ref_o).max() <= 1e-4
+            assert np.abs(lse.cpu().numpy() - ref_lse).max() <= 1e-4
+        else:
+            check_output(b.desc, o.cpu().numpy(), lse.cpu().numpy(), ref_o, ref_lse, f"c{cid} peaked tt={tt}")
+        db.plan.close()
