@@ -177,6 +177,7 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
     const int min_pages = env_int("NANOCP_PLAN_MIN_PAGES", 8, 1, 1 << 20);
     const double static_frac = env_int("NANOCP_PLAN_STATIC_PCT", mla ? 100 : 85, 1, 100) / 100.0;
     const int gss_k = env_int("NANOCP_PLAN_GSS_K", 2, 1, 64);
+    const int snap_pct = env_int("NANOCP_PLAN_SNAP_PCT", 12, 0, 50);  // measured: fewer tiles, same balance
     const int64_t M = std::max<int64_t>(1, (int64_t)num_cus * env_int("NANOCP_PLAN_WGS_PER_CU", 1, 1, 16));
 
     // longest shards first: the big, statically sized chunks at the head of the queue then hold the long
@@ -219,13 +220,18 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
           while (pg < pe) {
             // tail of the queue: a short (shard, head) is kept whole so that it needs no partials
             const bool whole = !fixed && p->dynamic && chunk >= M && pg == pb && (pe - pb) + c0 <= whole_max;
-            const int64_t need = whole ? (pe - pb) + c0 : c0 + 1;
+            // Snapping: a cut that would leave a sliver (of the chunk, or of the (shard, head)) costs a tile and a
+            // partial for little balance; within `snap` pages the cut moves to the nearer boundary instead.
+            const int64_t snap = (fixed || !p->dynamic) ? 0 : cap * snap_pct / 100;
+            const int64_t need = whole ? (pe - pb) + c0 : c0 + 1 + std::min<int64_t>(snap, pe - pg - 1);
             if (used > 0 && cap - used < need) {
               ++chunk;
               used = 0;
               cap = open_cap(chunk);
             }
-            const int take = whole ? pe - pb : (int)std::min<int64_t>(pe - pg, cap - used - c0);
+            int take = whole ? pe - pb : (int)std::min<int64_t>(pe - pg, cap - used - c0);
+            if (!whole && (pe - pg) - take <= snap) take = pe - pg;  // the rest is a sliver: keep it in this chunk
+
             nanocp_tile t;
             t.shard = s;
             t.kv_head = h;
