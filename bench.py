@@ -24,10 +24,10 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the tile kernel, from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a 1 GiB copy
 # (summaries and commands under profiles/); valid for the default plan of the named config only.
-MEASURED_TRAFFIC_BYTES = {3: (1205877004, "profiles/gqa_mfma_bf16_config3_mixed_dcp.md"),
-                          5: (770151075, "profiles/gqa_mfma_fp8_config5_long_shard.md"),
-                          2: (658320499, "profiles/gqa_mfma_bf16_config2_local.md"),
-                          4: (1609056635, "profiles/mla_mfma_bf16_config4.md")}
+MEASURED_TRAFFIC_BYTES = {3: (1203376213, "profiles/gqa_mfma_bf16_config3_mixed_dcp.md"),
+                          5: (764280881, "profiles/gqa_mfma_fp8_config5_long_shard.md"),
+                          2: (656013679, "profiles/gqa_mfma_bf16_config2_local.md"),
+                          4: (1592092833, "profiles/mla_mfma_bf16_config4.md")}
 METRIC = "decode-attention KV GB/s (% of HBM peak) + µs/step, mixed ragged DCP batch"
 WORKLOAD_NAMES = {1: "config1: tiny fp32 GQA", 2: "config2: bf16 GQA 64 local requests U[1024,8192]",
                   3: "config3: mixed long-tail DCP batch, 128 requests lognormal(median 2048, sigma 1.2), bf16 GQA 64q/4kv d128",
