@@ -143,7 +143,8 @@ void nanocp_plan_destroy(nanocp_plan* plan);
  *   workspace                                          DEVICE scratch of at least the queried size
  *                                                      (16-byte aligned; contents need not be preserved)
  * One launch on `stream` for the MFMA variants (the workgroup that delivers the last tile of a (shard, head)
- * also reduces its tile partials); the generic variant adds a small reduction launch.  A plan must not be
+ * also reduces its tile partials, and empty shards are filled by the same kernel); the MLA and generic variants
+ * add a small reduction launch.  A plan must not be
  * run concurrently on two streams: launches share the plan's work-queue counters.
  * Errors: EINVAL (null), ESTATE (plan not uploaded), EBOUNDS (workspace too small), EHIP.
  */

@@ -200,7 +200,9 @@ nanocp_status launch_tiles_and_reduce(const nanocp_attn_desc& d, int variant, co
       e = launch_gqa_mfma(variant, p, blocks, st);
     if (e != hipSuccess) return NANOCP_EHIP;
   }
-  if (num_segs > 0) {
+  // the fused variants' only segments are (shard, head) pairs without tokens, which their tile kernel fills itself
+  const bool fills_own = blocks > 0 && (variant == kGqaMfmaBf16 || variant == kGqaMfmaFp8);
+  if (num_segs > 0 && !fills_own) {
     if (p.Dv % 4) return NANOCP_ESHAPE;
     const unsigned per_seg = (unsigned)((p.G * (p.Dv / 4) + kThreads - 1) / kThreads);
     hipLaunchKernelGGL(reduce_tiles_kernel, dim3((unsigned)num_segs, per_seg), dim3(kThreads), 0, st, d_segs, p.ws_o,
@@ -253,6 +255,8 @@ nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_
   p.chunk_offsets = plan->d_chunk_offsets;
   p.sync = plan->d_sync;
   p.num_chunks = plan->num_chunks;
+  p.segs = plan->d_segs;
+  p.num_segs = (int)plan->segs.size();
   p.header = nullptr;
   p.tile_clock = tile_clock;
   p.final_out = final_out;
@@ -344,6 +348,8 @@ nanocp_status nanocp_decode_attn_partial_image(const nanocp_attn_desc* desc, con
   p.chunk_offsets = (const int32_t*)(img + L.chunk_offsets);
   p.sync = (int32_t*)(img + L.sync);
   p.num_chunks = 0;
+  p.segs = (const Seg*)(img + L.segs);
+  p.num_segs = 0;
   p.header = (const int32_t*)(img + L.header);
   p.tile_clock = nullptr;
   p.final_out = final_out;

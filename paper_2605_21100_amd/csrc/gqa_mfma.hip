@@ -523,6 +523,31 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
   chunk = __builtin_amdgcn_readfirstlane(next_s);
   __syncthreads();
   }
+  // (shard, head) pairs without tokens (the plan lists no others for this kernel): O = 0, LSE = -inf
+  {
+    const int num_segs = p.header ? as_const(p.header)[1] : p.num_segs;
+    const int n = tid >> 4, d0 = (tid & 15) * 8;
+    for (int si = blockIdx.x; si < num_segs; si += gridDim.x) {
+      const Seg sg = p.segs[si];
+      if (sg.n_parts != 0) continue;
+      const size_t head = (size_t)sg.kv_head * kG + n;
+      if ((tid & 15) == 0) p.out_lse[(size_t)sg.shard * p.Hq + head] = -INFINITY;
+      if (p.final_out && sg.final_row >= 0) {
+        const size_t fo = ((size_t)sg.final_row * p.Hq + head) * kD + d0;
+        if (p.final_bf16) {
+          *(u32x4*)((__bf16*)p.final_out + fo) = u32x4{0u, 0u, 0u, 0u};
+        } else {
+          *(f32x4*)((float*)p.final_out + fo) = f32x4{0.f, 0.f, 0.f, 0.f};
+          *(f32x4*)((float*)p.final_out + fo + 4) = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        if ((tid & 15) == 0 && p.final_lse) p.final_lse[(size_t)sg.final_row * p.Hq + head] = -INFINITY;
+      } else {
+        float* dst_o = p.out_o + ((size_t)sg.shard * p.Hq + head) * kD + d0;
+        *(f32x4*)dst_o = f32x4{0.f, 0.f, 0.f, 0.f};
+        *(f32x4*)(dst_o + 4) = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+  }
   // the last workgroup to leave re-arms the queue for the next launch
   if (tid == 0) {
     const int done = atomicAdd(&p.sync[1], 1);

@@ -54,7 +54,9 @@ struct KParams {
   const int32_t* chunk_offsets;
   int32_t* sync;         // plan-owned counters (see kSyncSegBase)
   int32_t num_chunks;
-  const int32_t* header;  // null, or the counts on the device (plan image): they then override num_chunks
+  const Seg* segs;       // segments without a tile of their own kernel pass (the fused variants fill the empty ones)
+  int32_t num_segs;
+  const int32_t* header;  // null, or the counts on the device (plan image): they then override num_chunks / num_segs
   uint64_t* tile_clock;   // may be null
   void* final_out;       // [num_out, Hq, Dv] float or bf16; null = every shard writes out_o / out_lse
   float* final_lse;      // [num_out, Hq], may be null

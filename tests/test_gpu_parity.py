@@ -137,6 +137,48 @@ def test_edge_ranges(kv_dtype):
         db.plan.close()
 
 
+@pytest.mark.parametrize("kv_dtype", ["f32", "bf16", "fp8", "mla"])
+def test_edge_ranges_as_final_rows(kv_dtype):
+    """The same hand-made ranges with every shard its own output row: empty shards become zero rows with LSE = -inf
+    straight from the attention launch (plan and plan-image entry points), the others equal partial + merge."""
+    _say(f"[case] edge ranges as final rows {kv_dtype}")
+    ps = 16 if kv_dtype == "f32" else 64
+    spec = [(0, 0), (0, 1), (3, ps - 2), (ps - 1, ps + 1), (2 * ps, 2 * ps), (0, 4 * ps), (7, 5 * ps + 9), (0, 0)]
+    b = _edge_batch(kv_dtype, spec)
+    S, d = b.num_shards, b.desc
+    base = nanocp.DeviceBatch(b)
+    o, lse = base.partial()
+    want, want_lse = _merge_on_gpu(base, o, lse)
+    db = nanocp.DeviceBatch(b, final_rows=True)
+    assert (db.shard_final_row >= 0).all() and len(db.rest_rows) == 0
+    bucket = nanocp.Bucket(db.plan.num_tiles + 8, db.plan.num_chunks + 8, db.plan.num_tiles + S * d.num_kv_heads + 8,
+                           db.plan.num_tiles + 8)
+    host_img = torch.empty(nanocp.bucket_plan_bytes(bucket), dtype=torch.uint8).pin_memory()
+    db.plan.pack(bucket, host_img)
+    dev_img = host_img.cuda()
+    ws = torch.empty(max(nanocp.bucket_workspace_bytes(db.desc, bucket), 16), dtype=torch.uint8, device="cuda")
+    for dt in (torch.float32, torch.bfloat16):
+        for image in (False, True):
+            out = torch.full((S, d.num_q_heads, d.head_dim_v), float("nan"), dtype=dt, device="cuda")
+            out_lse = torch.full((S, d.num_q_heads), float("nan"), device="cuda")
+            po, pl = torch.full_like(o, float("nan")), torch.full_like(lse, float("nan"))
+            if image:
+                nanocp.nanocp_decode_attn_partial_image(db.desc, bucket, dev_img, 0, b.block_table.shape[1], db.q,
+                                                        db.k_pool, db.v_pool, db.k_scale, db.v_scale, db.block_table,
+                                                        po, pl, ws, final_out=out, final_lse=out_lse)
+            else:
+                nanocp.nanocp_decode_attn_partial(db.plan, db.q, db.k_pool, db.v_pool, db.k_scale, db.v_scale,
+                                                  db.block_table, po, pl, db.workspace, final_out=out,
+                                                  final_lse=out_lse)
+            torch.cuda.synchronize()
+            assert torch.equal(out, want.to(dt)), f"{kv_dtype} {dt} image={image}"
+            assert torch.equal(out_lse, want_lse) and torch.equal(pl, lse)
+            for e in (0, 4, 7):
+                assert torch.all(out[e] == 0) and torch.all(torch.isneginf(out_lse[e]))
+    base.plan.close()
+    db.plan.close()
+
+
 def test_merge_edge_cases():
     """All-empty merge, identity (one part), parts ignored when LSE = -inf even if their output is NaN."""
     _say("[case] merge edge cases")
