@@ -142,10 +142,10 @@ void nanocp_plan_destroy(nanocp_plan* plan);
  *   out_o, out_lse                                     DEVICE, written for every shard
  *   workspace                                          DEVICE scratch of at least the queried size
  *                                                      (16-byte aligned; contents need not be preserved)
- * One launch on `stream` for the MFMA variants (the workgroup that delivers the last tile of a (shard, head)
+ * One launch on `stream` for the GQA MFMA variants (the workgroup that delivers the last tile of a (shard, head)
  * also reduces its tile partials, and empty shards are filled by the same kernel); the MLA and generic variants
- * add a small reduction launch.  A plan must not be
- * run concurrently on two streams: launches share the plan's work-queue counters.
+ * add a small reduction launch.  A plan must not be run concurrently on two streams: launches share the plan's
+ * work-queue counters.
  * Errors: EINVAL (null), ESTATE (plan not uploaded), EBOUNDS (workspace too small), EHIP.
  */
 nanocp_status nanocp_decode_attn_partial(const nanocp_plan* plan, const void* q, const void* k_pool,
