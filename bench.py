@@ -27,7 +27,9 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {3: (1203376213, "profiles/gqa_mfma_bf16_config3_mixed_dcp.md"),
                           5: (764280881, "profiles/gqa_mfma_fp8_config5_long_shard.md"),
                           2: (656013679, "profiles/gqa_mfma_bf16_config2_local.md"),
-                          4: (1592092833, "profiles/mla_mfma_bf16_config4.md")}
+                          4: (1592092833, "profiles/mla_mfma_bf16_config4.md"),
+                          6: (677223914, "profiles/gqa_mfma_bf16_config6_microbench.md"),   # 3 long requests per node
+                          7: (1470534140, "profiles/mla64_mfma_bf16_config7.md")}
 METRIC = "decode-attention KV GB/s (% of HBM peak) + µs/step, mixed ragged DCP batch"
 WORKLOAD_NAMES = {1: "config1: tiny fp32 GQA", 2: "config2: bf16 GQA 64 local requests U[1024,8192]",
                   3: "config3: mixed long-tail DCP batch, 128 requests lognormal(median 2048, sigma 1.2), bf16 GQA 64q/4kv d128",
@@ -300,7 +302,7 @@ def main():
                  "equal_chunk_us_mean": float(head.mean()), "equal_chunk_us_max": float(head.max()),
                  "straggle_equal_chunk_max_over_mean": float(head.max() / head.mean())}
 
-    default_plan = (args.tile_tokens == 0 and not args.merge_all and not args.graph and
+    default_plan = (args.tile_tokens == 0 and not args.merge_all and not args.graph and args.num_long == 3 and
                     not any(k.startswith("NANOCP_") for k in os.environ))
     traffic, traffic_src = (MEASURED_TRAFFIC_BYTES.get(args.config, (None, None)) if default_plan else (None, None))
     result = {
