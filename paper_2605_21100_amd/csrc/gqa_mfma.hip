@@ -473,7 +473,12 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) st_dev(dst_o + 16 * e, o[e]);
         if (c16 == 0) st_dev(p.ws_lse + (size_t)tile.dst * kG + n, lse_nat);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // own stores have completed (they write through)
+        // Every thread's device-scope stores must have been acknowledged before the arrival is counted: the
+        // workgroup-scope fence orders them for the compiler but waits for nothing on this target (one CU, one
+        // L1), and a store still in flight could be overtaken by the counter's atomic, which goes to another
+        // channel - the reducing workgroup would then read a stale partial.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
         if (tid == 0) arrive_s = atomicAdd(&p.sync[kSyncSegBase + tile.seg], 1);
         __syncthreads();
