@@ -250,6 +250,27 @@ def test_run_to_run_determinism():
     db.plan.close()
 
 
+@pytest.mark.parametrize("cid", [2, 5])
+def test_fused_reduction_is_stable_over_many_launches(cid):
+    """Full-size batch cut into 1024-token tiles (every long (shard, head) is reduced by the workgroup that delivers
+    its last tile, while the memory system is saturated): 100 launches, each bit-identical to the first.  A partial
+    that is counted as arrived before its stores have landed shows up here as a wrong row."""
+    _say(f"[case] repeated launches, full-size config {cid}, 1024-token tiles")
+    b = W.FULL[cid](with_remote_kv=False)
+    db = nanocp.DeviceBatch(b, tile_tokens=1024)
+    o0, l0 = (t.clone() for t in db.partial())
+    bad = torch.zeros((), dtype=torch.int64, device="cuda")
+    for _ in range(100):
+        o, lse = db.partial()
+        bad += (o != o0).any(dim=-1).sum() + (lse != l0).sum()
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0
+    ro, rl = oracle.attn_partial_paged(b.desc, b.q, b.k_pool, b.v_pool, b.k_scale, b.v_scale, b.block_table,
+                                       b.shards[0])
+    check_output(b.desc, o0[0].cpu().numpy(), l0[0].cpu().numpy(), ro, rl, f"c{cid} repeated launches, shard 0")
+    db.plan.close()
+
+
 def _sample_shards(b, k, rng):
     lens = b.shards[:, 3] - b.shards[:, 2]
     order = np.argsort(lens)
