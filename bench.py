@@ -24,11 +24,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the tile kernel, from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a 1 GiB copy
 # (summaries and commands under profiles/); valid for the default plan of the named config only.
-MEASURED_TRAFFIC_BYTES = {3: (1203376213, "profiles/gqa_mfma_bf16_config3_mixed_dcp.md"),
-                          5: (764280881, "profiles/gqa_mfma_fp8_config5_long_shard.md"),
-                          2: (656013679, "profiles/gqa_mfma_bf16_config2_local.md"),
+MEASURED_TRAFFIC_BYTES = {3: (1203393507, "profiles/gqa_mfma_bf16_config3_mixed_dcp.md"),
+                          5: (764291010, "profiles/gqa_mfma_fp8_config5_long_shard.md"),
+                          2: (656027840, "profiles/gqa_mfma_bf16_config2_local.md"),
                           4: (1592092833, "profiles/mla_mfma_bf16_config4.md"),
-                          6: (677223914, "profiles/gqa_mfma_bf16_config6_microbench.md"),   # 3 long requests per node
+                          6: (677224885, "profiles/gqa_mfma_bf16_config6_microbench.md"),   # 3 long requests per node
                           7: (1470534140, "profiles/mla64_mfma_bf16_config7.md")}
 METRIC = "decode-attention KV GB/s (% of HBM peak) + µs/step, mixed ragged DCP batch"
 WORKLOAD_NAMES = {1: "config1: tiny fp32 GQA", 2: "config2: bf16 GQA 64 local requests U[1024,8192]",
