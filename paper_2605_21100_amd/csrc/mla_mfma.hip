@@ -1,6 +1,6 @@
-// MFMA tile kernel for MLA-absorbed decode (DeepSeek-V3-like shapes; 64 heads with 4 wavefronts): 128 query heads share one latent
-// row of 576 dims per token (512 latent + 64 rope); V is the first 512 dims of the same row, so a page is
-// read from HBM once and used for both products.  bf16, page size 64.
+// MFMA tile kernel for MLA-absorbed decode (DeepSeek-V3-like shapes): 128 query heads (or 64, with 4 wavefronts)
+// share one latent row of 576 dims per token (512 latent + 64 rope); V is the first 512 dims of the same row, so a
+// page is read from HBM once and used for both products.  bf16, page size 64.
 // Paper: Data Plane, Phase 2 (partial attention + LSE over the local KV partition); the MoE-bound
 // instance's Q row has hidden size 512 (+64) and 128 heads.
 //
@@ -32,7 +32,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kDk = 576, kDv = 512, kPS = 64;
-constexpr int kHB = 1;  // 16-head blocks per wavefront
+constexpr int kHB = 1;  // 16-head blocks per wavefront (2 was measured: half the LDS reads, but Q and O no longer fit 256 registers)
 // kKD, kVD below: how far the LDS reads run ahead of the matrix instructions that use them (K: units of two
 // fragments, V: fragments); bounded by the registers left beside Q and the accumulators: (1, 2) with 256 registers
 // per wavefront.  Measured with 512 registers (64-head variant): going deeper than this does not help -- the
@@ -197,7 +197,7 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
                 dst + (uint32_t)(kRegionA + (kSlabs * wave + a) * 1024));
       };
 
-      // Q fragments of this wavefront's 32 heads (B operand): lane (g, n = r) holds Q[16hb + n][dims 8(4s+g) .. +8]
+      // Q fragments of this wavefront's heads (B operand): lane (g, n = r) holds Q[16hb + n][dims 8(4s+g) .. +8]
       bf16x8 qf[kHB][kSteps];
 #pragma unroll
       for (int hb = 0; hb < kHB; ++hb) {
@@ -241,16 +241,16 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
           wg_barrier();
         }
 
-        // ---- scores S^T[16 tokens x 16 heads] for the 4 token blocks of the page and both head blocks;
-        // every K fragment feeds two MFMAs, and the 8 accumulators give the matrix pipe independent work
+        // ---- scores S^T[16 tokens x 16 heads] for the 4 token blocks of the page (x kHB head blocks): independent
+        // accumulators, so consecutive matrix instructions do not wait for each other
         f32x4 S[4][kHB];
 #pragma unroll
         for (int tbk = 0; tbk < 4; ++tbk)
 #pragma unroll
           for (int hb = 0; hb < kHB; ++hb) S[tbk][hb] = f32x4{0.f, 0.f, 0.f, 0.f};
-        // software pipeline over the k-steps: the 4 fragments of step s+1 are read while the 8 MFMAs of step s
-        // run; scheduling barriers keep the compiler from hoisting all LDS reads to the top (register blow-up)
-        // unit u = (k-step s, token-block pair): 2 fragments, 2*kHB MFMAs
+        // software pipeline over units u = (k-step s, token-block pair) of 2 fragments and 2*kHB MFMAs: the
+        // fragments of unit u+kKD are read while the MFMAs of unit u run; scheduling barriers keep the compiler
+        // from hoisting all LDS reads to the top (register blow-up)
         auto load_k = [&](bf16x8* kf, int u) {
           const int s = u >> 1;
 #pragma unroll
@@ -320,10 +320,8 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
           split8(y + 8, hi[hb][1], lo[hb][1]);
         }
 
-        // ---- O^T += V^T P^T: every V fragment (two transpose reads) feeds four MFMAs; the two fragments of
-        // dim block dvb+1 are read while the 8 MFMAs of dim block dvb run
-        // unit u = (dim block dvb, token half j): one fragment (two transpose reads), 2*kHB MFMAs; three units of
-        // fragments are kept in flight
+        // ---- O^T += V^T P^T over units u = (dim block dvb, token half j): one fragment (two transpose reads) feeds
+        // 2*kHB MFMAs (hi and lo term of P); kVD fragments are kept in flight
         auto load_v = [&](int u) {
           const int dvb = u >> 1, j = u & 1;
           u32x4 vf;
@@ -357,7 +355,7 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         wg_barrier();  // the buffer may be overwritten by the copy issued at the top of the next iteration
       }
 
-      // ---- write this wavefront's 32 heads: normalised output rows and natural-log LSE
+      // ---- write this wavefront's heads: normalised output rows and natural-log LSE
       float* dst_o;
       float* dst_l;
       if (tile.dst >= 0) {
