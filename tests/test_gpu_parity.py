@@ -271,6 +271,37 @@ def test_fused_reduction_is_stable_over_many_launches(cid):
     db.plan.close()
 
 
+@pytest.mark.parametrize("cid", [1, 2, 4, 5])
+def test_pages_beyond_4_gib_into_the_pool(cid):
+    """Maximum sizes: the same batch with its pages moved to the end of pools larger than 4 GiB (page ids shifted in the
+    block table) must give bit-identical results - byte offsets into the pools need 64 bits."""
+    _say(f"[case] pool offsets beyond 4 GiB, reduced config {cid}")
+    b = W.reduced(cid)
+    db = nanocp.DeviceBatch(b)
+    o_ref, lse_ref = (t.clone() for t in db.partial())
+
+    def grow(t, n_big):
+        if t is None:
+            return None
+        big = torch.empty((n_big,) + tuple(t.shape[1:]), dtype=t.dtype, device="cuda")
+        big[n_big - t.shape[0]:] = t
+        return big
+
+    pages = db.k_pool.shape[0]
+    page_bytes = db.k_pool[0].numel() * db.k_pool.element_size()
+    n_big = (5 << 30) // page_bytes + pages
+    shift = n_big - pages
+    assert shift * page_bytes > 1 << 32
+    k, v = grow(db.k_pool, n_big), grow(db.v_pool, n_big)
+    ks, vs = grow(db.k_scale, n_big), grow(db.v_scale, n_big)
+    bt = db.block_table + shift
+    o, lse = torch.empty_like(o_ref), torch.empty_like(lse_ref)
+    nanocp.nanocp_decode_attn_partial(db.plan, db.q, k, v, ks, vs, bt, o, lse, db.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(o, o_ref) and torch.equal(lse, lse_ref)
+    db.plan.close()
+
+
 def _sample_shards(b, k, rng):
     lens = b.shards[:, 3] - b.shards[:, 2]
     order = np.argsort(lens)
