@@ -72,8 +72,21 @@ def test_merged_equals_gpu_unsharded(cid):
     """The GPU's merge of its own d partials against the GPU's own single-shard run of the same request."""
     _say(f"[case] merged vs unsharded, reduced config {cid}")
     b = W.reduced(cid, hold_all=True) if cid in (3, 5, 6) else W.reduced(cid)
+    _merged_vs_unsharded(b, 256 if b.desc.page_size <= 64 else 0)
+
+
+def test_merged_equals_gpu_unsharded_full_size_long_request():
+    """Config 5's 1,048,576-token fp8 request with all 8 shards on this GPU (automatic tiling, as benchmarked): the
+    merge of the 8 partials against one unsharded pass over the million tokens."""
+    _say("[case] merged vs unsharded, full-size config 5 request (1,048,576 tokens, CP = 8)")
+    b = W.FULL[5](num_short=16, hold_all=True, with_remote_kv=False)
+    assert int(b.shards[:8, 3].max()) == 1048576
+    _merged_vs_unsharded(b, 0)
+
+
+def _merged_vs_unsharded(b, tile_tokens):
     assert len(b.remote_meta) == 0
-    db = nanocp.DeviceBatch(b, tile_tokens=256 if b.desc.page_size <= 64 else 0)
+    db = nanocp.DeviceBatch(b, tile_tokens=tile_tokens)
     o, lse = db.partial()
     out, out_lse = _merge_on_gpu(db, o, lse)
     # unsharded: one shard per request covering all its tokens, on the same pools / block table
