@@ -288,19 +288,24 @@ def main():
         n_wg = int(wg.max()) + 1
         finish = np.zeros(n_wg)
         np.maximum.at(finish, wg, (c[:, 1] - t0) / 100.0)            # 100 MHz clock -> microseconds
-        # the first n_wg chunks of the queue have equal cost by construction: their run times are the
-        # "tile times" whose spread says how much one piece of the work-list can straggle
+        # the first n_wg chunks of the queue are the big, statically sized ones (equal cost up to the planner's
+        # boundary snapping, +-12 %): their run times, raw and per token, are the "tile times" whose spread says
+        # how much one piece of the work-list can straggle
         nch = plan_t.num_chunks
         c_start = np.full(nch, np.iinfo(np.int64).max)
         c_end = np.zeros(nch, np.int64)
         np.minimum.at(c_start, tiles["chunk"], c[:, 0])
         np.maximum.at(c_end, tiles["chunk"], c[:, 1])
         head = ((c_end - c_start) / 100.0)[:min(n_wg, nch)]
+        c_tok = np.zeros(nch)
+        np.add.at(c_tok, tiles["chunk"], tiles["tok_end"] - tiles["tok_begin"])
+        rate = head / np.maximum(c_tok[:len(head)], 1)               # microseconds per token of the chunk
         extra = {"chunks": int(nch), "tiles": int(db.plan.num_tiles), "workgroups": n_wg,
                  "wg_finish_us_mean": float(finish.mean()), "wg_finish_us_max": float(finish.max()),
                  "straggle_wg_finish_max_over_mean": float(finish.max() / finish.mean()),
                  "equal_chunk_us_mean": float(head.mean()), "equal_chunk_us_max": float(head.max()),
-                 "straggle_equal_chunk_max_over_mean": float(head.max() / head.mean())}
+                 "straggle_equal_chunk_max_over_mean": float(head.max() / head.mean()),
+                 "straggle_equal_chunk_per_token_max_over_mean": float(rate.max() / rate.mean())}
 
     default_plan = (args.tile_tokens == 0 and not args.merge_all and not args.graph and args.num_long == 3 and
                     not any(k.startswith("NANOCP_") for k in os.environ))
