@@ -241,6 +241,22 @@ nanocp_status nanocp_merge_partials_dyn(const nanocp_attn_desc* desc, const floa
                                         const int32_t* num_out_dev, const int32_t* out_rows, void* out,
                                         int32_t out_dtype, float* out_lse, void* stream);
 
+/*
+ * nanocp_kv_append -- the writer that goes with the paged layouts above: stores the K / V rows of n tokens at
+ * (block-table row, token position) into the pools.  A decode step appends one token per request to the local KV
+ * before Phase 2 (each instance keeps only its own KV partition; paper: Data Plane); one bulk call converts a plain
+ * cache into the layouts the attention kernels read.
+ *   k_new     DEVICE [n, Hkv, Dk] kv elements (MLA: [n, Dk]), 16-byte aligned
+ *   v_new     DEVICE [n, Hkv, Dv] kv elements (NULL for MLA: V is part of the latent row)
+ *   bt_row, position   DEVICE int32 [n]; the page is block_table[bt_row][position / ps] and must exist
+ * fp8: bytes are stored as given, the per-(page, head) scales stay with the caller.  Entries naming the same
+ * (row, position) race.  Asynchronous on `stream`.  Errors: EINVAL, ESHAPE, EUNSUPPORTED (as nanocp_plan_create
+ * for the shape), EBOUNDS (more than 2^31 blocks), EHIP.
+ */
+nanocp_status nanocp_kv_append(const nanocp_attn_desc* desc, const void* k_new, const void* v_new,
+                               const int32_t* bt_row, const int32_t* position, int32_t n, void* k_pool, void* v_pool,
+                               const int32_t* block_table, int32_t max_blocks_per_row, void* stream);
+
 const char* nanocp_status_str(nanocp_status s);
 
 #ifdef __cplusplus

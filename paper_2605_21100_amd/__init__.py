@@ -45,7 +45,7 @@ EXPORTS = ["nanocp_plan_create", "nanocp_plan_query", "nanocp_plan_tiles", "nano
            "nanocp_decode_attn_partial_timed", "nanocp_merge_partials", "nanocp_status_str",
            "nanocp_plan_set_final_rows", "nanocp_decode_attn_partial_final", "nanocp_merge_partials_rows",
            "nanocp_bucket_plan_bytes", "nanocp_bucket_workspace_bytes", "nanocp_plan_pack",
-           "nanocp_decode_attn_partial_image", "nanocp_merge_partials_dyn"]
+           "nanocp_decode_attn_partial_image", "nanocp_merge_partials_dyn", "nanocp_kv_append"]
 
 
 class Bucket(ctypes.Structure):
@@ -86,6 +86,7 @@ def _load():
     lib.nanocp_decode_attn_partial_image.argtypes = ([ctypes.POINTER(AttnDesc), ctypes.POINTER(Bucket), vp, i32, i32] +
                                                      [vp] * 8 + [vp, sz, vp, i32, vp, vp])
     lib.nanocp_merge_partials_dyn.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, i32, vp, vp, vp, i32, vp, vp]
+    lib.nanocp_kv_append.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, i32, vp, vp, vp, i32, vp]
     lib.nanocp_status_str.argtypes = [ctypes.c_int]
     lib.nanocp_status_str.restype = ctypes.c_char_p
     return lib
@@ -293,6 +294,13 @@ def desc_from(d):
     """AttnDesc from any object with the generator's field names."""
     return make_desc(d.kind, d.q_dtype, d.kv_dtype, d.num_q_heads, d.num_kv_heads, d.head_dim_qk,
                      d.head_dim_v, d.page_size, d.softmax_scale)
+
+
+def nanocp_kv_append(desc, k_new, v_new, bt_row, position, k_pool, v_pool, block_table, stream=None):
+    """Store n tokens' K / V rows at (block-table row, position) into the paged pools (the layouts' writer)."""
+    _check(_lib.nanocp_kv_append(ctypes.byref(desc), _ptr(k_new), _ptr(v_new), _ptr(bt_row), _ptr(position),
+                                 int(bt_row.numel()), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+                                 int(block_table.shape[1]), _stream(stream)), "nanocp_kv_append")
 
 
 def to_device(arr, kind=None, device="cuda"):

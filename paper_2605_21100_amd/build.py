@@ -5,7 +5,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["plan.cpp", "sched.cpp", "generic.hip", "gqa_mfma.hip", "mla_mfma.hip", "api.hip"]
+SOURCES = ["plan.cpp", "sched.cpp", "generic.hip", "gqa_mfma.hip", "mla_mfma.hip", "kv_append.hip", "api.hip"]
 LIB = os.path.join(HERE, "libnanocp.so")
 
 

@@ -20,7 +20,9 @@ namespace {
 
 int elem_bytes(int dt) { return dt == NANOCP_F32 ? 4 : dt == NANOCP_BF16 ? 2 : 1; }
 
-nanocp_status check_desc(const nanocp_attn_desc& d) {
+}  // namespace
+
+nanocp_status nanocp::check_desc(const nanocp_attn_desc& d) {
   if (d.kind != NANOCP_GQA && d.kind != NANOCP_MLA) return NANOCP_EINVAL;
   if (d.q_dtype < 0 || d.q_dtype > 2 || d.kv_dtype < 0 || d.kv_dtype > 2) return NANOCP_EINVAL;
   if (d.num_q_heads <= 0 || d.num_kv_heads <= 0 || d.head_dim_qk <= 0 || d.head_dim_v <= 0 || d.page_size <= 0)
@@ -42,8 +44,6 @@ nanocp_status check_desc(const nanocp_attn_desc& d) {
   if (d.head_dim_qk > 576 || d.head_dim_v > 512) return NANOCP_EUNSUPPORTED;  // generic kernel's LDS/register budget
   return NANOCP_OK;
 }
-
-}  // namespace
 
 int nanocp::pick_variant(const nanocp_attn_desc& d) {
   const int G = d.num_q_heads / d.num_kv_heads;

@@ -9,6 +9,7 @@ namespace nanocp {
 
 enum Variant : int32_t { kGeneric = 0, kGqaMfmaBf16 = 1, kGqaMfmaFp8 = 2, kMlaMfmaBf16 = 3 };
 int pick_variant(const nanocp_attn_desc& d);  // which tile kernel handles this problem shape
+nanocp_status check_desc(const nanocp_attn_desc& d);  // shape / dtype checks shared by the host entry points
 
 // Reduction segment: the tile partials of one (shard, kv head).  Only segments with
 // n_parts != 1 exist (0 parts = empty shard, filled with O = 0 / LSE = -inf).
