@@ -18,7 +18,7 @@
 extern "C" {
 #endif
 
-#define NANOCP_SCHED_MAX_CP 8 /* a KV binding stays inside one node (Alg. 1 line 8: k_r <= |S_n*|) */
+#define NANOCP_SCHED_MAX_CP 8 /* a KV binding stays inside one node (Alg. 1, choice of k_r: k_r <= |S_n*|) */
 
 typedef struct {
   int32_t num_nodes;
@@ -43,14 +43,14 @@ typedef struct {
  * one token each to the lowest-indexed participants at that level. */
 nanocp_status nanocp_sched_water_fill(int32_t n, const int64_t* loads, int64_t length, int64_t* split);
 
-/* Alg. 1 lines 1-5: rebalance the MoE bindings of the active requests.  Request r's participants are
+/* Alg. 1, first part (rebalancing the active requests): rebalance the MoE bindings of the active requests.  Request r's participants are
  * part_instances[part_offsets[r] .. part_offsets[r+1]).  Requests are taken by ascending participant count;
  * each is bound to its participant with the fewest bound requests so far.
  * Writes moe_instance[num_active] and moe_load[S] (B_s, starting from zero). */
 nanocp_status nanocp_sched_rebalance(const nanocp_sched_config* cfg, int32_t num_active, const int32_t* part_offsets,
                                      const int32_t* part_instances, int32_t* moe_instance, int32_t* moe_load);
 
-/* Alg. 1 lines 6-18: place the new requests in order.  kv_load[S] (K_s) and moe_load[S] (B_s) are read and
+/* Alg. 1, second part (placing the new requests): place them in order.  kv_load[S] (K_s) and moe_load[S] (B_s) are read and
  * updated by every committed placement.  Writes decisions[num_new]. */
 nanocp_status nanocp_sched_place(const nanocp_sched_config* cfg, int64_t* kv_load, int32_t* moe_load, int32_t num_new,
                                  const int64_t* lengths, nanocp_sched_decision* decisions);
