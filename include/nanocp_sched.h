@@ -43,7 +43,7 @@ typedef struct {
  * one token each to the lowest-indexed participants at that level. */
 nanocp_status nanocp_sched_water_fill(int32_t n, const int64_t* loads, int64_t length, int64_t* split);
 
-/* Alg. 1, first part (rebalancing the active requests): rebalance the MoE bindings of the active requests.  Request r's participants are
+/* Alg. 1, first part: rebalance the MoE bindings of the active requests.  Request r's participants are
  * part_instances[part_offsets[r] .. part_offsets[r+1]).  Requests are taken by ascending participant count;
  * each is bound to its participant with the fewest bound requests so far.
  * Writes moe_instance[num_active] and moe_load[S] (B_s, starting from zero). */
