@@ -101,6 +101,7 @@ def main():
     import torch
     import paper_2605_21100_amd as nanocp
     import workloads as W
+    from workloads.device import DeviceBatch
 
     torch.cuda.set_device(0)
     if args.calibrate_copy:
@@ -120,7 +121,7 @@ def main():
     kw = {"num_long": args.num_long} if args.config == 6 else {}
     batch = W.FULL[args.config](with_remote_kv=False, **kw)
     d = batch.desc
-    db = nanocp.DeviceBatch(batch, tile_tokens=args.tile_tokens, final_rows=not args.merge_all)
+    db = DeviceBatch(batch, tile_tokens=args.tile_tokens, final_rows=not args.merge_all)
     pools = [(db.k_pool, db.v_pool, db.k_scale, db.v_scale)]
     pools.append(tuple(None if t is None else t.clone() for t in pools[0]))
     S, R = batch.num_shards, batch.num_requests

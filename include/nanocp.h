@@ -35,6 +35,13 @@
  *   out_lse      [num_shards, Hq]     float        natural-log LSE of the shard's scaled scores
  * An empty shard (kv_begin == kv_end) yields out_o = 0, out_lse = -inf.  Token slots of a page
  * outside [kv_begin, kv_end) may hold anything (NaN included); they are masked.
+ *
+ * Kernels.  Matrix-core (MFMA) tile kernels exist for exactly these shapes:
+ *   GQA  q bf16, kv bf16 or fp8, Hq / Hkv = 16, Dk = Dv = 128, ps = 64      ("gqa_mfma_bf16", "gqa_mfma_fp8")
+ *   MLA  q bf16, kv bf16, Hq = 128 or 64, Dk = 576, Dv = 512, ps = 64       ("mla_mfma_bf16")
+ * Every other supported shape (any head counts, Dk <= 576, Dv <= 512, any page size the layout admits, f32 / bf16 /
+ * fp8 KV; fp8 MLA is not supported at all) runs a plain fp32 kernel ("generic") that is correct but orders of
+ * magnitude slower; nanocp_plan_kernel tells which one a plan uses.
  */
 #ifndef NANOCP_H
 #define NANOCP_H
@@ -72,6 +79,9 @@ typedef struct {
   int32_t head_dim_v;    /* Dv (MLA: Dv <= Dk) */
   int32_t page_size;     /* ps, tokens per page */
   float softmax_scale;   /* score = softmax_scale * <q, k> */
+  float out_scale;       /* FP8 output rows only (out_dtype / final_dtype = NANOCP_FP8_E4M3): the stored code is
+                            e4m3(value / out_scale), round to nearest even, saturating at +-448 -- a static scale the
+                            caller supplies, as consumers of fp8 activations do.  0 means 1.  Ignored otherwise. */
 } nanocp_attn_desc;
 
 /* One shard entry = one row of the attention batch of this instance: a whole local request, or
@@ -153,15 +163,6 @@ nanocp_status nanocp_decode_attn_partial(const nanocp_plan* plan, const void* q,
                                          const int32_t* block_table, float* out_o, float* out_lse,
                                          void* workspace, size_t workspace_bytes, void* stream);
 
-/* Same, and additionally records per tile {device wall clock (100 MHz ticks) at its start, at its end, index of
- * the workgroup that ran it} into tile_clock[num_tiles][3] (DEVICE, uint64) -- used to report how much the
- * slowest workgroup straggles behind the mean. */
-nanocp_status nanocp_decode_attn_partial_timed(const nanocp_plan* plan, const void* q, const void* k_pool,
-                                               const void* v_pool, const float* k_scale, const float* v_scale,
-                                               const int32_t* block_table, float* out_o, float* out_lse,
-                                               void* workspace, size_t workspace_bytes, uint64_t* tile_clock,
-                                               void* stream);
-
 /*
  * nanocp_merge_partials -- Phase 4: LSE-based merge.  For output r and head a, over the partials
  * i in part_index[part_offsets[r] .. part_offsets[r+1]):
@@ -169,9 +170,11 @@ nanocp_status nanocp_decode_attn_partial_timed(const nanocp_plan* plan, const vo
  *   o_parts    DEVICE [num_parts, Hq, Dv] float   (local partials from nanocp_decode_attn_partial and/or
  *   lse_parts  DEVICE [num_parts, Hq]     float    partials received from other instances)
  *   part_offsets DEVICE [num_out + 1] int32; part_index DEVICE [part_offsets[num_out]] int32, or NULL for identity
- *   out        DEVICE [num_out, Hq, Dv] of out_dtype (NANOCP_F32 or NANOCP_BF16)
+ *   out        DEVICE [num_out, Hq, Dv] of out_dtype: NANOCP_F32, NANOCP_BF16, or NANOCP_FP8_E4M3 (one byte per
+ *              element, the code of value / desc->out_scale; see nanocp_attn_desc)
  *   out_lse    DEVICE [num_out, Hq] float, or NULL
- * Partials with lse = -inf are ignored; if all are, O = 0 and LSE = -inf.  Only Hq and Dv of desc are used.
+ * Partials with lse = -inf are ignored; if all are, O = 0 and LSE = -inf.  Only Hq, Dv and out_scale of desc are
+ * used.
  */
 nanocp_status nanocp_merge_partials(const nanocp_attn_desc* desc, const float* o_parts, const float* lse_parts,
                                     const int32_t* part_offsets, const int32_t* part_index, int32_t num_out,
@@ -183,10 +186,12 @@ nanocp_status nanocp_merge_partials(const nanocp_attn_desc* desc, const float* o
  * shard_final_row[s] = r >= 0 declares that every partial of output row r (r < num_out) is a shard of this plan and
  * s is one of them (usually the only one; several shards may name the same row -- a request split over shards that
  * are all local -- and are then reduced together), -1 otherwise.  The call re-derives the partial slots: query the
- * workspace size after it.  nanocp_decode_attn_partial_final then writes the final row final_out[r] (NANOCP_F32 or
- * NANOCP_BF16, [num_out, Hq, Dv], DEVICE, 16-byte aligned) and final_lse[r] ([num_out, Hq] float, may be NULL)
- * straight from the kernel that finishes it; the out_o rows of those shards are NOT written (out_lse is, but means
- * the row's LSE when shards share a row, and a plan with such shards only runs through this entry point).  All
+ * workspace size after it.  nanocp_decode_attn_partial_final then writes the final row final_out[r] (NANOCP_F32,
+ * NANOCP_BF16 or NANOCP_FP8_E4M3 as in nanocp_merge_partials, [num_out, Hq, Dv], DEVICE, 16-byte aligned) and
+ * final_lse[r] ([num_out, Hq] float, may be NULL) straight from the kernel that finishes it; the out_o rows of those
+ * shards are NOT written.  out_lse is: for a shard that is alone in its row it is the shard's (= the row's) LSE; for
+ * shards that share a row, the row's LSE is written at the FIRST shard naming the row and the out_lse rows of the
+ * others are left untouched (a plan with such shards only runs through this entry point).  All
  * other shards behave as in nanocp_decode_attn_partial.  The remaining output rows are merged with nanocp_merge_partials_rows:
  * like nanocp_merge_partials over num_out partial lists, list i producing row out_rows[i] (DEVICE int32, NULL =
  * identity) of out / out_lse.
@@ -215,7 +220,9 @@ nanocp_status nanocp_merge_partials_rows(const nanocp_attn_desc* desc, const flo
  * every image of the bucket, so it can be captured in a HIP graph together with nanocp_merge_partials_dyn (the
  * row-indexed merge over at most max_out lists, the actual count read from *num_out_dev on the device).
  * num_cus workgroups are launched whatever the batch is (0 = query the current device).  final_out may be NULL.
- * One image must not be in use by two launches at a time (it holds the work-queue counters).
+ * One image must not be in use by two launches at a time (it holds the work-queue counters).  The kernels compare
+ * the image's header with the call: an image packed for another kernel variant, or one whose shards are grouped into
+ * final rows while final_out is NULL, is not run (the outputs stay untouched).
  * Errors: EBOUNDS if the plan exceeds the bucket or a buffer is too small; otherwise as the calls they mirror.
  */
 typedef struct {

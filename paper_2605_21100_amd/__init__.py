@@ -24,7 +24,7 @@ class AttnDesc(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("q_dtype", ctypes.c_int32), ("kv_dtype", ctypes.c_int32),
                 ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
                 ("head_dim_qk", ctypes.c_int32), ("head_dim_v", ctypes.c_int32),
-                ("page_size", ctypes.c_int32), ("softmax_scale", ctypes.c_float)]
+                ("page_size", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("out_scale", ctypes.c_float)]
 
 
 class Shard(ctypes.Structure):
@@ -42,10 +42,11 @@ TILE_DTYPE = np.dtype([(n, np.int32) for n, _ in Tile._fields_])
 
 EXPORTS = ["nanocp_plan_create", "nanocp_plan_query", "nanocp_plan_tiles", "nanocp_plan_kernel",
            "nanocp_plan_upload", "nanocp_plan_destroy", "nanocp_decode_attn_partial",
-           "nanocp_decode_attn_partial_timed", "nanocp_merge_partials", "nanocp_status_str",
+           "nanocp_merge_partials", "nanocp_status_str",
            "nanocp_plan_set_final_rows", "nanocp_decode_attn_partial_final", "nanocp_merge_partials_rows",
            "nanocp_bucket_plan_bytes", "nanocp_bucket_workspace_bytes", "nanocp_plan_pack",
            "nanocp_decode_attn_partial_image", "nanocp_merge_partials_dyn", "nanocp_kv_append"]
+DEBUG_EXPORTS = ["nanocp_decode_attn_partial_timed"]          # include/nanocp_debug.h
 
 
 class Bucket(ctypes.Structure):
@@ -107,9 +108,21 @@ def _check(status, where):
 
 
 def make_desc(kind, q_dtype, kv_dtype, num_q_heads, num_kv_heads, head_dim_qk, head_dim_v, page_size,
-              softmax_scale):
+              softmax_scale, out_scale=0.0):
     return AttnDesc(_KINDS.get(kind, kind), _DTYPES.get(q_dtype, q_dtype), _DTYPES.get(kv_dtype, kv_dtype),
-                    num_q_heads, num_kv_heads, head_dim_qk, head_dim_v, page_size, softmax_scale)
+                    num_q_heads, num_kv_heads, head_dim_qk, head_dim_v, page_size, softmax_scale, out_scale)
+
+
+def _out_dtype(t, where):
+    """nanocp_dtype of an output tensor: float32, bfloat16, or one byte per element (uint8 / float8_e4m3fn) for fp8."""
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.uint8 or t.dtype == getattr(torch, "float8_e4m3fn", None):
+        return FP8_E4M3
+    raise NanocpError(EUNSUPPORTED, where)
 
 
 def _ptr(t):
@@ -199,17 +212,15 @@ def nanocp_plan(desc, shards, num_q_rows, num_bt_rows, max_blocks_per_row, tile_
 def nanocp_decode_attn_partial(plan, q, k_pool, v_pool, k_scale, v_scale, block_table, out_o, out_lse,
                                workspace, tile_clock=None, stream=None, final_out=None, final_lse=None):
     """Phase 2 on the given torch device tensors; results land in out_o / out_lse (float32).  With final_out
-    (float32 or bfloat16 [num_out, Hq, Dv]) shards that are a whole output row write it directly."""
+    (float32, bfloat16 or fp8 bytes, [num_out, Hq, Dv]) shards that are a whole output row write it directly."""
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     args = [plan._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(k_scale), _ptr(v_scale), _ptr(block_table),
             _ptr(out_o), _ptr(out_lse), _ptr(workspace), ws_bytes]
     if final_out is not None:
-        import torch
         assert tile_clock is None
-        if final_out.dtype not in (torch.bfloat16, torch.float32):
-            raise NanocpError(EUNSUPPORTED, "nanocp_decode_attn_partial_final")
-        _check(_lib.nanocp_decode_attn_partial_final(*args, _ptr(final_out), BF16 if final_out.dtype == torch.bfloat16
-                                                     else F32, _ptr(final_lse), _stream(stream)),
+        _check(_lib.nanocp_decode_attn_partial_final(*args, _ptr(final_out),
+                                                     _out_dtype(final_out, "nanocp_decode_attn_partial_final"),
+                                                     _ptr(final_lse), _stream(stream)),
                "nanocp_decode_attn_partial_final")
     elif tile_clock is None:
         _check(_lib.nanocp_decode_attn_partial(*args, _stream(stream)), "nanocp_decode_attn_partial")
@@ -220,12 +231,9 @@ def nanocp_decode_attn_partial(plan, q, k_pool, v_pool, k_scale, v_scale, block_
 
 def nanocp_merge_partials(desc, o_parts, lse_parts, part_offsets, part_index, num_out, out, out_lse=None,
                           stream=None, out_rows=None):
-    """Phase 4 on device tensors; out is float32 or bfloat16 [rows, Hq, Dv].  With out_rows (int32 [num_out]) list i
-    of the CSR produces row out_rows[i] instead of row i."""
-    import torch
-    out_dtype = BF16 if out.dtype == torch.bfloat16 else F32
-    if out.dtype not in (torch.bfloat16, torch.float32):
-        raise NanocpError(EUNSUPPORTED, "nanocp_merge_partials")
+    """Phase 4 on device tensors; out is float32, bfloat16 or fp8 bytes [rows, Hq, Dv].  With out_rows (int32
+    [num_out]) list i of the CSR produces row out_rows[i] instead of row i."""
+    out_dtype = _out_dtype(out, "nanocp_merge_partials")
     if out_rows is None:
         _check(_lib.nanocp_merge_partials(ctypes.byref(desc), _ptr(o_parts), _ptr(lse_parts), _ptr(part_offsets),
                                           _ptr(part_index), num_out, _ptr(out), out_dtype, _ptr(out_lse),
@@ -248,9 +256,8 @@ def nanocp_decode_attn_partial_image(desc, bucket, image, num_cus, max_blocks_pe
                                      v_scale, block_table, out_o, out_lse, workspace, final_out=None, final_lse=None,
                                      stream=None):
     """Phase 2 driven by a plan image on the device (same call for every plan of the bucket: graph-capturable)."""
-    import torch
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    fdt = BF16 if (final_out is not None and final_out.dtype == torch.bfloat16) else F32
+    fdt = F32 if final_out is None else _out_dtype(final_out, "nanocp_decode_attn_partial_image")
     _check(_lib.nanocp_decode_attn_partial_image(ctypes.byref(desc), ctypes.byref(bucket), _ptr(image), num_cus,
                                                  max_blocks_per_row, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(k_scale),
                                                  _ptr(v_scale), _ptr(block_table), _ptr(out_o), _ptr(out_lse),
@@ -261,8 +268,7 @@ def nanocp_decode_attn_partial_image(desc, bucket, image, num_cus, max_blocks_pe
 def nanocp_merge_partials_dyn(desc, o_parts, lse_parts, part_offsets, part_index, max_out, num_out_dev, out_rows, out,
                               out_lse=None, stream=None):
     """Row-indexed merge over at most max_out lists; the count is read from num_out_dev (int32 [1]) on the device."""
-    import torch
-    out_dtype = BF16 if out.dtype == torch.bfloat16 else F32
+    out_dtype = _out_dtype(out, "nanocp_merge_partials_dyn")
     _check(_lib.nanocp_merge_partials_dyn(ctypes.byref(desc), _ptr(o_parts), _ptr(lse_parts), _ptr(part_offsets),
                                           _ptr(part_index), max_out, _ptr(num_out_dev), _ptr(out_rows), _ptr(out),
                                           out_dtype, _ptr(out_lse), _stream(stream)), "nanocp_merge_partials_dyn")
@@ -288,64 +294,11 @@ def split_final_rows(part_offsets, part_index, num_local, single_only=False):
     return final, np.asarray(offs, np.int32), np.asarray(idx, np.int32), np.asarray(rows, np.int32)
 
 
-# --------------------------------------------------------------------------- convenience for tests / bench
-
-def desc_from(d):
-    """AttnDesc from any object with the generator's field names."""
-    return make_desc(d.kind, d.q_dtype, d.kv_dtype, d.num_q_heads, d.num_kv_heads, d.head_dim_qk,
-                     d.head_dim_v, d.page_size, d.softmax_scale)
-
-
 def nanocp_kv_append(desc, k_new, v_new, bt_row, position, k_pool, v_pool, block_table, stream=None):
     """Store n tokens' K / V rows at (block-table row, position) into the paged pools (the layouts' writer)."""
     _check(_lib.nanocp_kv_append(ctypes.byref(desc), _ptr(k_new), _ptr(v_new), _ptr(bt_row), _ptr(position),
                                  int(bt_row.numel()), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
                                  int(block_table.shape[1]), _stream(stream)), "nanocp_kv_append")
-
-
-def to_device(arr, kind=None, device="cuda"):
-    """numpy raw buffer -> torch device tensor of the matching element type (bf16 bits, fp8 bytes)."""
-    import torch
-    if arr is None:
-        return None
-    if arr.dtype == np.uint16:
-        return torch.from_numpy(arr.view(np.int16)).to(device).view(torch.bfloat16)
-    if arr.dtype == np.uint8:
-        return torch.from_numpy(arr).to(device)
-    return torch.from_numpy(arr).to(device)
-
-
-class DeviceBatch:
-    """A synthetic batch resident in HBM plus its plan, outputs and workspace."""
-
-    def __init__(self, batch, tile_tokens=0, num_cus=0, device="cuda", final_rows=False, single_only=False):
-        import torch
-        self.batch = batch
-        d = batch.desc
-        self.desc = desc_from(d)
-        self.q = to_device(batch.q, device=device)
-        self.k_pool = to_device(batch.k_pool, device=device)
-        self.v_pool = to_device(batch.v_pool, device=device)
-        self.k_scale = to_device(batch.k_scale, device=device)
-        self.v_scale = to_device(batch.v_scale, device=device)
-        self.block_table = to_device(batch.block_table, device=device)
-        S = batch.shards.shape[0]
-        self.plan = Plan(self.desc, batch.shards, batch.q.shape[0], batch.block_table.shape[0],
-                         batch.block_table.shape[1], tile_tokens, num_cus)
-        if final_rows:      # single-shard local requests skip the merge
-            fin, self.rest_offsets, self.rest_index, self.rest_rows = split_final_rows(
-                batch.part_offsets, batch.part_index, S, single_only)
-            self.plan.set_final_rows(fin, batch.num_requests)
-            self.shard_final_row = fin
-        self.plan.upload()
-        self.out_o = torch.empty((S, d.num_q_heads, d.head_dim_v), dtype=torch.float32, device=device)
-        self.out_lse = torch.empty((S, d.num_q_heads), dtype=torch.float32, device=device)
-        self.workspace = torch.empty(max(self.plan.workspace_bytes, 16), dtype=torch.uint8, device=device)
-
-    def partial(self, tile_clock=None):
-        nanocp_decode_attn_partial(self.plan, self.q, self.k_pool, self.v_pool, self.k_scale, self.v_scale,
-                                   self.block_table, self.out_o, self.out_lse, self.workspace, tile_clock)
-        return self.out_o, self.out_lse
 
 
 # --------------------------------------------------------------------------- host scheduler (include/nanocp_sched.h)

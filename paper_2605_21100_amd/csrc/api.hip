@@ -3,6 +3,8 @@
 // Paper: Data Plane, Phase 2 (partial attention + LSE) and Phase 4 (LSE-based merging).
 #include <hip/hip_runtime.h>
 
+#include "epilogue.h"
+#include "nanocp_debug.h"
 #include "plan.h"
 
 namespace nanocp {
@@ -13,13 +15,6 @@ hipError_t launch_mla_mfma(const KParams& p, int num_blocks, hipStream_t st);
 
 namespace {
 
-__device__ inline uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-
 // LSE-combine of the tile partials of one (shard, kv head): the same operator as the Phase 4 merge,
 // applied inside the instance (used by the variants that do not reduce inside the tile kernel, and to
 // fill empty shards).  One thread per 4 output dims; parts are taken 8 at a time with a running maximum.
@@ -28,7 +23,8 @@ __global__ __launch_bounds__(kThreads) void reduce_tiles_kernel(const Seg* __res
                                                                 const float* __restrict__ ws_lse,
                                                                 float* __restrict__ out_o, float* __restrict__ out_lse,
                                                                 void* __restrict__ final_out,
-                                                                float* __restrict__ final_lse, int final_bf16,
+                                                                float* __restrict__ final_lse, int final_kind,
+                                                                float out_scale,
                                                                 const int32_t* __restrict__ header, int Hq, int G,
                                                                 int Dv) {
   if (header && (int)blockIdx.x >= header[1]) return;  // plan image: launched for the bucket's capacity
@@ -79,14 +75,8 @@ __global__ __launch_bounds__(kThreads) void reduce_tiles_kernel(const Seg* __res
   if (final_out && sg.final_row >= 0) {
     // the shard is the only partial of its output row: final form, no merge needed
     const size_t fi = ((size_t)sg.final_row * Hq + (size_t)sg.kv_head * G) * Dv + (size_t)i4 * 4;
-    if (final_bf16) {
-      uint2 pk;
-      pk.x = (uint32_t)f32_to_bf16_rne(acc[0] * inv) | ((uint32_t)f32_to_bf16_rne(acc[1] * inv) << 16);
-      pk.y = (uint32_t)f32_to_bf16_rne(acc[2] * inv) | ((uint32_t)f32_to_bf16_rne(acc[3] * inv) << 16);
-      *(uint2*)((uint16_t*)final_out + fi) = pk;
-    } else {
-      *(float4*)((float*)final_out + fi) = make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
-    }
+    const float o4[4] = {acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
+    store_final<4>(final_out, fi, final_kind, out_scale, o4);
     if (final_lse && (i4 % q4) == 0) final_lse[(size_t)sg.final_row * Hq + (size_t)sg.kv_head * G + g] = lse;
     return;
   }
@@ -96,14 +86,14 @@ __global__ __launch_bounds__(kThreads) void reduce_tiles_kernel(const Seg* __res
 
 // Phase 4: per (output, head) merge of the partials named by the CSR lists.
 // One thread per 4 consecutive output dims, so each thread has a single short chain of dependent loads.
-template <bool kBf16Out>
 __global__ __launch_bounds__(kThreads) void merge_kernel(const float* __restrict__ o_parts,
                                                          const float* __restrict__ lse_parts,
                                                          const int32_t* __restrict__ part_offsets,
                                                          const int32_t* __restrict__ part_index,
                                                          const int32_t* __restrict__ out_rows,
                                                          const int32_t* __restrict__ num_out_dev, void* __restrict__ out,
-                                                         float* __restrict__ out_lse, int Hq, int Dv) {
+                                                         float* __restrict__ out_lse, int out_kind, float out_scale,
+                                                         int Hq, int Dv) {
   if (num_out_dev && (int)blockIdx.x >= *num_out_dev) return;  // launched for a capacity, the count is on the device
   const int b = part_offsets[blockIdx.x], e = part_offsets[blockIdx.x + 1];
   const int r = out_rows ? out_rows[blockIdx.x] : (int)blockIdx.x;  // output row of this list
@@ -176,14 +166,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float* __restrict
     lse = top + logf(tot);
   }
   const size_t oi = (size_t)r * row + (size_t)i4 * 4;
-  if (kBf16Out) {
-    uint2 pk;
-    pk.x = (uint32_t)f32_to_bf16_rne(acc[0]) | ((uint32_t)f32_to_bf16_rne(acc[1]) << 16);
-    pk.y = (uint32_t)f32_to_bf16_rne(acc[2]) | ((uint32_t)f32_to_bf16_rne(acc[3]) << 16);
-    *(uint2*)((uint16_t*)out + oi) = pk;
-  } else {
-    *(float4*)((float*)out + oi) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-  }
+  store_final<4>(out, oi, out_kind, out_scale, acc);
   if (out_lse && (i4 % q4) == 0) out_lse[(size_t)r * Hq + a] = lse;
 }
 
@@ -206,7 +189,7 @@ nanocp_status launch_tiles_and_reduce(const nanocp_attn_desc& d, int variant, co
     if (p.Dv % 4) return NANOCP_ESHAPE;
     const unsigned per_seg = (unsigned)((p.G * (p.Dv / 4) + kThreads - 1) / kThreads);
     hipLaunchKernelGGL(reduce_tiles_kernel, dim3((unsigned)num_segs, per_seg), dim3(kThreads), 0, st, d_segs, p.ws_o,
-                       p.ws_lse, p.out_o, p.out_lse, p.final_out, p.final_lse, p.final_bf16, p.header, p.Hq, p.G, p.Dv);
+                       p.ws_lse, p.out_o, p.out_lse, p.final_out, p.final_lse, p.final_kind, p.out_scale, p.header, p.Hq, p.G, p.Dv);
     if (hipGetLastError() != hipSuccess) return NANOCP_EHIP;
   }
   return NANOCP_OK;
@@ -218,7 +201,7 @@ nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_
                           int32_t final_dtype, float* final_lse, void* stream) {
   if (!plan) return NANOCP_EINVAL;
   if (final_out) {
-    if (final_dtype != NANOCP_F32 && final_dtype != NANOCP_BF16) return NANOCP_EUNSUPPORTED;
+    if (!final_dtype_ok(final_dtype)) return NANOCP_EUNSUPPORTED;
     if (plan->num_final_rows == 0) return NANOCP_ESTATE;  // nanocp_plan_set_final_rows was not called
     if ((uintptr_t)final_out & 15) return NANOCP_EINVAL;
     if (plan->desc.head_dim_v % 8) return NANOCP_ESHAPE;
@@ -261,7 +244,9 @@ nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_
   p.tile_clock = tile_clock;
   p.final_out = final_out;
   p.final_lse = final_out ? final_lse : nullptr;
-  p.final_bf16 = final_dtype == NANOCP_BF16;
+  p.final_kind = final_out ? final_dtype : NANOCP_F32;
+  p.out_scale = out_scale_of(d);
+  p.variant = plan->variant;
   p.Hq = d.num_q_heads;
   p.Hkv = d.num_kv_heads;
   p.G = G;
@@ -274,6 +259,73 @@ nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_
 
   return launch_tiles_and_reduce(d, plan->variant, p, plan->num_chunks > 0 ? plan->launch_blocks : 0, plan->d_segs,
                                  (int)plan->segs.size(), st);
+}
+
+// Phase 2 driven by a plan image on the device: every count is read from the image's header by the kernels.
+nanocp_status run_image(const nanocp_attn_desc* desc, const nanocp_bucket* bucket, const void* device_image,
+                        int32_t num_cus, int32_t max_blocks_per_row, const void* q, const void* k_pool,
+                        const void* v_pool, const float* k_scale, const float* v_scale, const int32_t* block_table,
+                        float* out_o, float* out_lse, void* workspace, size_t workspace_bytes, void* final_out,
+                        int32_t final_dtype, float* final_lse, void* stream) {
+  if (!desc || !bucket || !device_image || num_cus <= 0 || max_blocks_per_row < 0) return NANOCP_EINVAL;
+  if (bucket->max_tiles < 0 || bucket->max_chunks < 0 || bucket->max_segs < 0 || bucket->max_slots < 0)
+    return NANOCP_EINVAL;
+  const nanocp_attn_desc& d = *desc;
+  const nanocp_status ds = check_desc(d);  // the kernels' LDS and register arrays are sized for the checked limits
+  if (ds != NANOCP_OK) return ds;
+  if (d.head_dim_v % 4) return NANOCP_ESHAPE;
+  if (!q || !k_pool || !block_table || !out_o || !out_lse) return NANOCP_EINVAL;
+  if (d.kind == NANOCP_GQA && !v_pool) return NANOCP_EINVAL;
+  if (d.kv_dtype == NANOCP_FP8_E4M3 && (!k_scale || !v_scale)) return NANOCP_EINVAL;
+  if (final_out && !final_dtype_ok(final_dtype)) return NANOCP_EUNSUPPORTED;
+  if (final_out && d.head_dim_v % 8) return NANOCP_ESHAPE;
+  const size_t ws_need = nanocp_bucket_workspace_bytes(desc, bucket);
+  if (ws_need > 0 && (!workspace || workspace_bytes < ws_need)) return NANOCP_EBOUNDS;
+  if (((uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)workspace | (uintptr_t)out_o |
+       (uintptr_t)final_out) & 15)
+    return NANOCP_EINVAL;
+  if ((uintptr_t)device_image & 255) return NANOCP_EINVAL;
+  const int variant = pick_variant(d);
+  const ImageLayout L = image_layout(*bucket);
+  const char* img = (const char*)device_image;
+  const int G = d.num_q_heads / d.num_kv_heads;
+  KParams p;
+  p.q = q;
+  p.k_pool = k_pool;
+  p.v_pool = v_pool;
+  p.k_scale = k_scale;
+  p.v_scale = v_scale;
+  p.block_table = block_table;
+  p.out_o = out_o;
+  p.out_lse = out_lse;
+  p.ws_o = (float*)workspace;
+  p.ws_lse = (float*)((char*)workspace + align256((size_t)bucket->max_slots * G * d.head_dim_v * sizeof(float)));
+  p.tiles = (const DevTile*)(img + L.tiles);
+  p.chunk_offsets = (const int32_t*)(img + L.chunk_offsets);
+  p.sync = (int32_t*)(img + L.sync);
+  p.num_chunks = 0;
+  p.segs = (const Seg*)(img + L.segs);
+  p.num_segs = 0;
+  p.header = (const int32_t*)(img + L.header);
+  p.tile_clock = nullptr;
+  p.final_out = final_out;
+  p.final_lse = final_out ? final_lse : nullptr;
+  p.final_kind = final_out ? final_dtype : NANOCP_F32;
+  p.out_scale = out_scale_of(d);
+  p.variant = variant;
+  p.Hq = d.num_q_heads;
+  p.Hkv = d.num_kv_heads;
+  p.G = G;
+  p.Dk = d.head_dim_qk;
+  p.Dv = d.head_dim_v;
+  p.ps = d.page_size;
+  p.max_blocks = max_blocks_per_row;
+  p.kind = d.kind;
+  p.scale = d.softmax_scale;
+  // dynamic variants: one workgroup per compute unit pulls chunks; the generic kernel runs one workgroup per chunk
+  const int blocks = variant == kGeneric ? bucket->max_chunks : num_cus;
+  return launch_tiles_and_reduce(d, variant, p, blocks, (const Seg*)(img + L.segs), bucket->max_segs,
+                                 (hipStream_t)stream);
 }
 
 }  // namespace
@@ -306,68 +358,15 @@ nanocp_status nanocp_decode_attn_partial_image(const nanocp_attn_desc* desc, con
                                                const int32_t* block_table, float* out_o, float* out_lse,
                                                void* workspace, size_t workspace_bytes, void* final_out,
                                                int32_t final_dtype, float* final_lse, void* stream) {
-  using namespace nanocp;
-  if (!desc || !bucket || !device_image || num_cus < 0 || max_blocks_per_row < 0) return NANOCP_EINVAL;
-  if (bucket->max_tiles < 0 || bucket->max_chunks < 0 || bucket->max_segs < 0 || bucket->max_slots < 0)
-    return NANOCP_EINVAL;
-  const nanocp_attn_desc& d = *desc;
-  if (d.num_q_heads <= 0 || d.num_kv_heads <= 0 || d.num_q_heads % d.num_kv_heads) return NANOCP_ESHAPE;
-  if (!q || !k_pool || !block_table || !out_o || !out_lse) return NANOCP_EINVAL;
-  if (d.kind == NANOCP_GQA && !v_pool) return NANOCP_EINVAL;
-  if (d.kv_dtype == NANOCP_FP8_E4M3 && (!k_scale || !v_scale)) return NANOCP_EINVAL;
-  if (final_out && final_dtype != NANOCP_F32 && final_dtype != NANOCP_BF16) return NANOCP_EUNSUPPORTED;
-  if (final_out && d.head_dim_v % 8) return NANOCP_ESHAPE;
-  const size_t ws_need = nanocp_bucket_workspace_bytes(desc, bucket);
-  if (ws_need > 0 && (!workspace || workspace_bytes < ws_need)) return NANOCP_EBOUNDS;
-  if (((uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)workspace | (uintptr_t)out_o |
-       (uintptr_t)final_out) & 15)
-    return NANOCP_EINVAL;
-  if ((uintptr_t)device_image & 255) return NANOCP_EINVAL;
   if (num_cus == 0) {
     int dev = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return NANOCP_EHIP;
     num_cus = prop.multiProcessorCount;
   }
-  const int variant = pick_variant(d);
-  const ImageLayout L = image_layout(*bucket);
-  const char* img = (const char*)device_image;
-  const int G = d.num_q_heads / d.num_kv_heads;
-  KParams p;
-  p.q = q;
-  p.k_pool = k_pool;
-  p.v_pool = v_pool;
-  p.k_scale = k_scale;
-  p.v_scale = v_scale;
-  p.block_table = block_table;
-  p.out_o = out_o;
-  p.out_lse = out_lse;
-  p.ws_o = (float*)workspace;
-  p.ws_lse = (float*)((char*)workspace + align256((size_t)bucket->max_slots * G * d.head_dim_v * sizeof(float)));
-  p.tiles = (const DevTile*)(img + L.tiles);
-  p.chunk_offsets = (const int32_t*)(img + L.chunk_offsets);
-  p.sync = (int32_t*)(img + L.sync);
-  p.num_chunks = 0;
-  p.segs = (const Seg*)(img + L.segs);
-  p.num_segs = 0;
-  p.header = (const int32_t*)(img + L.header);
-  p.tile_clock = nullptr;
-  p.final_out = final_out;
-  p.final_lse = final_out ? final_lse : nullptr;
-  p.final_bf16 = final_dtype == NANOCP_BF16;
-  p.Hq = d.num_q_heads;
-  p.Hkv = d.num_kv_heads;
-  p.G = G;
-  p.Dk = d.head_dim_qk;
-  p.Dv = d.head_dim_v;
-  p.ps = d.page_size;
-  p.max_blocks = max_blocks_per_row;
-  p.kind = d.kind;
-  p.scale = d.softmax_scale;
-  // dynamic variants: one workgroup per compute unit pulls chunks; the generic kernel runs one workgroup per chunk
-  const int blocks = variant == kGeneric ? bucket->max_chunks : num_cus;
-  return launch_tiles_and_reduce(d, variant, p, blocks, (const Seg*)(img + L.segs), bucket->max_segs,
-                                 (hipStream_t)stream);
+  return nanocp::run_image(desc, bucket, device_image, num_cus, max_blocks_per_row, q, k_pool, v_pool, k_scale,
+                           v_scale, block_table, out_o, out_lse, workspace, workspace_bytes, final_out, final_dtype,
+                           final_lse, stream);
 }
 
 nanocp_status nanocp_decode_attn_partial_timed(const nanocp_plan* plan, const void* q, const void* k_pool,
@@ -401,7 +400,7 @@ nanocp_status nanocp_merge_partials_dyn(const nanocp_attn_desc* desc, const floa
                                         int32_t out_dtype, float* out_lse, void* stream) {
   if (!desc || num_out < 0) return NANOCP_EINVAL;
   if (desc->num_q_heads <= 0 || desc->head_dim_v <= 0) return NANOCP_EINVAL;
-  if (out_dtype != NANOCP_F32 && out_dtype != NANOCP_BF16) return NANOCP_EUNSUPPORTED;
+  if (!nanocp::final_dtype_ok(out_dtype)) return NANOCP_EUNSUPPORTED;
   if (num_out == 0) return NANOCP_OK;
   if (!o_parts || !lse_parts || !part_offsets || !out) return NANOCP_EINVAL;
   const int Hq = desc->num_q_heads, Dv = desc->head_dim_v;
@@ -410,12 +409,8 @@ nanocp_status nanocp_merge_partials_dyn(const nanocp_attn_desc* desc, const floa
   const int per_out = (Hq * (Dv / 4) + nanocp::kThreads - 1) / nanocp::kThreads;
   dim3 grid((unsigned)num_out, (unsigned)per_out);
   hipStream_t st = (hipStream_t)stream;
-  if (out_dtype == NANOCP_BF16)
-    hipLaunchKernelGGL((nanocp::merge_kernel<true>), grid, dim3(nanocp::kThreads), 0, st, o_parts, lse_parts,
-                       part_offsets, part_index, out_rows, num_out_dev, out, out_lse, Hq, Dv);
-  else
-    hipLaunchKernelGGL((nanocp::merge_kernel<false>), grid, dim3(nanocp::kThreads), 0, st, o_parts, lse_parts,
-                       part_offsets, part_index, out_rows, num_out_dev, out, out_lse, Hq, Dv);
+  hipLaunchKernelGGL(nanocp::merge_kernel, grid, dim3(nanocp::kThreads), 0, st, o_parts, lse_parts, part_offsets,
+                     part_index, out_rows, num_out_dev, out, out_lse, out_dtype, nanocp::out_scale_of(*desc), Hq, Dv);
   return hipGetLastError() == hipSuccess ? NANOCP_OK : NANOCP_EHIP;
 }
 

@@ -5,6 +5,7 @@
 // Paper: Data Plane, Phase 2 (partial attention output and its LSE over the local KV partition).
 #include <hip/hip_runtime.h>
 
+#include "epilogue.h"
 #include "plan.h"
 
 namespace nanocp {
@@ -51,7 +52,10 @@ __global__ __launch_bounds__(kThreads) void generic_partial_kernel(KParams p) {
   const bool fp8 = sizeof(KT) == 1;
   const int Dk = p.Dk, Dv = p.Dv, ps = p.ps, Hkv = p.Hkv, G = p.G;
 
-  if (p.header && (int)blockIdx.x >= p.header[0]) return;  // plan image: launched for the bucket's capacity
+  // plan image: launched for the bucket's capacity; an image of another kernel variant, or one with grouped final
+  // rows but no final output, is not run
+  if (p.header && ((int)blockIdx.x >= p.header[0] || p.header[4] != p.variant || (p.header[5] != 0 && !p.final_out)))
+    return;
   const int t0 = p.chunk_offsets[blockIdx.x], t1 = p.chunk_offsets[blockIdx.x + 1];
   for (int ti = t0; ti < t1; ++ti) {
     const DevTile tile = p.tiles[ti];
@@ -161,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void generic_partial_kernel(KParams p) {
         dst_l = p.ws_lse + (size_t)tile.dst * G + g0;
       } else {
         dst_o = p.out_o + ((size_t)tile.shard * p.Hq + a0) * Dv;
-        dst_l = p.out_lse + (size_t)tile.shard * p.Hq + a0;
+        dst_l = p.out_lse + (size_t)tile.lse_shard * p.Hq + a0;
       }
       const bool fin = tile.dst < 0 && p.final_out && tile.final_row >= 0;  // the shard alone is an output row
       if (fin) {
@@ -171,8 +175,8 @@ __global__ __launch_bounds__(kThreads) void generic_partial_kernel(KParams p) {
           const int o = tid + i * kThreads;
           if (o < GH * Dv) {
             const float v = acc[i] / l_s[o / Dv];
-            if (p.final_bf16) ((__bf16*)p.final_out)[fo + o] = (__bf16)v;
-            else ((float*)p.final_out)[fo + o] = v;
+            const float v1[1] = {v};
+            store_final<1>(p.final_out, fo + o, p.final_kind, p.out_scale, v1);
           }
         }
         if (tid < GH) {

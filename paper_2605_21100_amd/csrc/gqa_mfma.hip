@@ -25,6 +25,7 @@
 #include <cstdlib>
 #include <type_traits>
 
+#include "epilogue.h"
 #include "plan.h"
 
 namespace nanocp {
@@ -172,10 +173,13 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
     const cptr<int32_t> w = tile_words + (size_t)ti * (sizeof(DevTile) / 4);
     t.q_row = w[0], t.bt_row = w[1], t.kv_head = w[2], t.shard = w[3];
     t.tok_begin = w[4], t.tok_end = w[5], t.dst = w[6], t.seg = w[7];
-    t.n_parts = w[8], t.slot_begin = w[9], t.final_row = w[10];
+    t.n_parts = w[8], t.slot_begin = w[9], t.final_row = w[10], t.lse_shard = w[11];
     return t;
   };
-  const int num_chunks = p.header ? as_const(p.header)[0] : p.num_chunks;  // plan image: the count lives on the device
+  // plan image: the counts live on the device.  An image packed for another kernel variant, or one whose shards
+  // are grouped into final rows while no final rows were given, is not run at all (outputs stay untouched).
+  if (p.header && (as_const(p.header)[4] != p.variant || (as_const(p.header)[5] != 0 && !p.final_out))) return;
+  const int num_chunks = p.header ? as_const(p.header)[0] : p.num_chunks;
   for (int chunk = blockIdx.x; chunk < num_chunks;) {
   const int t0 = chunk_offsets[chunk], t1 = chunk_offsets[chunk + 1];
   DevTile tile_next = load_tile(t0);
@@ -443,17 +447,11 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
             o[4 + e] = fmaf(f[w], b[e], o[4 + e]);
           }
         }
-        if (c16 == 0) p.out_lse[(size_t)tile.shard * p.Hq + (size_t)h * kG + n] = lse_nat;
+        if (c16 == 0) p.out_lse[(size_t)tile.lse_shard * p.Hq + (size_t)h * kG + n] = lse_nat;
         if (p.final_out && tile.final_row >= 0) {
           // the shard alone is an output row: written in its final form, no merge needed
           const size_t fo = ((size_t)tile.final_row * p.Hq + (size_t)h * kG + n) * kD + d0;
-          if (p.final_bf16) {
-            *(u32x4*)((__bf16*)p.final_out + fo) =
-                u32x4{pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]), pack_bf16(o[4], o[5]), pack_bf16(o[6], o[7])};
-          } else {
-            *(f32x4*)((float*)p.final_out + fo) = f32x4{o[0], o[1], o[2], o[3]};
-            *(f32x4*)((float*)p.final_out + fo + 4) = f32x4{o[4], o[5], o[6], o[7]};
-          }
+          store_final<8>(p.final_out, fo, p.final_kind, p.out_scale, o);
           if (c16 == 0 && p.final_lse) p.final_lse[(size_t)tile.final_row * p.Hq + (size_t)h * kG + n] = lse_nat;
         } else {
           float* dst_o = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG + n) * kD + d0;
@@ -498,13 +496,14 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
           }
           const float rinv = 1.f / tot;
           const float lse_f = top + logf(tot);
-          if (c16 == 0) p.out_lse[(size_t)tile.shard * p.Hq + (size_t)h * kG + n] = lse_f;
+          // (shards reduced as one group deliver the row's LSE at the group's first shard, whoever arrives last)
+          if (c16 == 0) p.out_lse[(size_t)tile.lse_shard * p.Hq + (size_t)h * kG + n] = lse_f;
           if (p.final_out && tile.final_row >= 0) {
             const size_t fi = ((size_t)tile.final_row * p.Hq + (size_t)h * kG + n) * kD + c16;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-              if (p.final_bf16) ((__bf16*)p.final_out)[fi + 16 * e] = (__bf16)(r8[e] * rinv);
-              else ((float*)p.final_out)[fi + 16 * e] = r8[e] * rinv;
+              const float v1[1] = {r8[e] * rinv};
+              store_final<1>(p.final_out, fi + 16 * e, p.final_kind, p.out_scale, v1);
             }
             if (c16 == 0 && p.final_lse) p.final_lse[(size_t)tile.final_row * p.Hq + (size_t)h * kG + n] = lse_f;
           } else {
@@ -539,12 +538,7 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
       if ((tid & 15) == 0) p.out_lse[(size_t)sg.shard * p.Hq + head] = -INFINITY;
       if (p.final_out && sg.final_row >= 0) {
         const size_t fo = ((size_t)sg.final_row * p.Hq + head) * kD + d0;
-        if (p.final_bf16) {
-          *(u32x4*)((__bf16*)p.final_out + fo) = u32x4{0u, 0u, 0u, 0u};
-        } else {
-          *(f32x4*)((float*)p.final_out + fo) = f32x4{0.f, 0.f, 0.f, 0.f};
-          *(f32x4*)((float*)p.final_out + fo + 4) = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
+        store_final_zero<8>(p.final_out, fo, p.final_kind);
         if ((tid & 15) == 0 && p.final_lse) p.final_lse[(size_t)sg.final_row * p.Hq + head] = -INFINITY;
       } else {
         float* dst_o = p.out_o + ((size_t)sg.shard * p.Hq + head) * kD + d0;
@@ -567,10 +561,16 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
 
 hipError_t launch_gqa_mfma(int variant, const KParams& p, int num_blocks, hipStream_t st) {
   dim3 grid(num_blocks), block(kThreads);
+  // K/V are read exactly once: the streaming (non-temporal) loads are the product path.  A -DNANOCP_TUNING build can
+  // switch them off from the environment to measure what they buy.
+#ifdef NANOCP_TUNING
   static const bool nt = [] {
     const char* v = std::getenv("NANOCP_KV_NONTEMPORAL");
     return !(v && v[0] == '0');
   }();
+#else
+  constexpr bool nt = true;
+#endif
   if (variant == kGqaMfmaBf16) {
     if (nt)
       hipLaunchKernelGGL((gqa_mfma_kernel<false, true>), grid, block, 0, st, p);

@@ -1,6 +1,6 @@
 // Writer for the paged KV layouts the attention kernels read (include/nanocp.h, "Memory layouts"): scatters the
-// K / V rows of n tokens into their pages.  A decode step appends one token per request before Phase 2 (paper:
-// Data Plane, each instance "stores and processes only its local KV shard"); a bulk call converts a plain cache.
+// K / V rows of n tokens into their pages.  A decode step appends one token per request to the instance's own KV
+// partition before Phase 2 (paper: Data Plane, per-instance KV partition); a bulk call converts a plain cache.
 // Pure data movement: one thread per 16-byte vector of the source rows.
 #include <hip/hip_runtime.h>
 

@@ -16,8 +16,9 @@
 // LDS rows are XOR-swizzled in units of 16 bytes so that both read patterns are bank-conflict free.
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
+#include <mutex>
 
+#include "epilogue.h"
 #include "plan.h"
 
 namespace nanocp {
@@ -38,12 +39,7 @@ constexpr int kHB = 1;  // 16-head blocks per wavefront (2 was measured: half th
 // per wavefront.  Measured with 512 registers (64-head variant): going deeper than this does not help -- the
 // transpose read itself is the limit (about 100 B/clk per CU against 210 for 16-byte reads, measured with a
 // stand-alone probe), and it carries 64 KB per wavefront and page.
-#ifndef NANOCP_MLA64_KD
-#define NANOCP_MLA64_KD 2
-#endif
-#ifndef NANOCP_MLA64_VD
-#define NANOCP_MLA64_VD 4
-#endif
+constexpr int kMla64KD = 2, kMla64VD = 4;
 constexpr int kRowBytes = kDk * 2;        // 1152: one token's latent row in HBM
 constexpr int kRowA = kDv * 2;            // 1024: dims 0..511 (the V part), LDS region A row
 constexpr int kRowB = (kDk - kDv) * 2;    // 128:  dims 512..575 (rope part), LDS region B row
@@ -162,7 +158,10 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
   }
   const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
 
-  const int num_chunks = p.header ? as_const(p.header)[0] : p.num_chunks;  // plan image: the count lives on the device
+  // plan image: the counts live on the device; an image of another kernel variant, or one with grouped final rows
+  // but no final output, is not run
+  if (p.header && (as_const(p.header)[4] != p.variant || (as_const(p.header)[5] != 0 && !p.final_out))) return;
+  const int num_chunks = p.header ? as_const(p.header)[0] : p.num_chunks;
   for (int chunk = blockIdx.x; chunk < num_chunks;) {
     const int t0 = chunk_offsets[chunk], t1 = chunk_offsets[chunk + 1];
     for (int ti = t0; ti < t1; ++ti) {
@@ -171,7 +170,7 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         const cptr<int32_t> w = tile_words + (size_t)ti * (sizeof(DevTile) / 4);
         tile.q_row = w[0], tile.bt_row = w[1], tile.kv_head = w[2], tile.shard = w[3];
         tile.tok_begin = w[4], tile.tok_end = w[5], tile.dst = w[6], tile.seg = w[7];
-        tile.n_parts = w[8], tile.slot_begin = w[9], tile.final_row = w[10];
+        tile.n_parts = w[8], tile.slot_begin = w[9], tile.final_row = w[10], tile.lse_shard = w[11];
       }
       uint64_t clk0 = 0;
       if (p.tile_clock && tid == 0) clk0 = wall_clock64();
@@ -363,7 +362,7 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         dst_l = p.ws_lse + (size_t)tile.dst * kHq;
       } else {
         dst_o = p.out_o + (size_t)tile.shard * kHq * kDv;
-        dst_l = p.out_lse + (size_t)tile.shard * kHq;
+        dst_l = p.out_lse + (size_t)tile.lse_shard * kHq;
       }
       const bool fin = tile.dst < 0 && p.final_out && tile.final_row >= 0;  // the shard alone is an output row
 #pragma unroll
@@ -379,12 +378,8 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
 #pragma unroll
           for (int dvb = 0; dvb < kDv / 16; ++dvb) {
             const f32x4 v = acc[hb][dvb] * inv;
-            if (p.final_bf16) {
-              u32x2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-              *(u32x2*)((__bf16*)p.final_out + fo + 16 * dvb) = pk;
-            } else {
-              *(f32x4*)((float*)p.final_out + fo + 16 * dvb) = v;
-            }
+            const float v4[4] = {v[0], v[1], v[2], v[3]};
+            store_final<4>(p.final_out, fo + 16 * dvb, p.final_kind, p.out_scale, v4);
             if ((dvb & 3) == 3) __builtin_amdgcn_sched_barrier(0);
           }
           if (g == 0 && p.final_lse) p.final_lse[(size_t)tile.final_row * kHq + head] = lse;
@@ -424,20 +419,38 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 }
 // 64 heads: one wavefront per SIMD, 512 registers: the LDS reads run far ahead
 __global__ __launch_bounds__(256, 1) void mla64_mfma_kernel(KParams p) {
-  mla_mfma_body<4, NANOCP_MLA64_KD, NANOCP_MLA64_VD>(p);
+  mla_mfma_body<4, kMla64KD, kMla64VD>(p);
+}
+
+// The dynamic-LDS limit is an attribute of the kernel on ONE device: it is raised once per device and kernel, with
+// that device current, the first time the kernel is launched there.
+template <typename K>
+hipError_t allow_big_lds(K kernel, int bytes, int slot) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static bool done[2][kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!done[slot][dev]) {
+    e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    done[slot][dev] = true;
+  }
+  return hipSuccess;
 }
 
 }  // namespace
 
 hipError_t launch_mla_mfma(const KParams& p, int num_blocks, hipStream_t st) {
   if (p.Hq == 128) {
-    static const hipError_t attr = hipFuncSetAttribute((const void*)mla_mfma_kernel,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kBufBytes);
+    const hipError_t attr = allow_big_lds(mla_mfma_kernel, 2 * kBufBytes, 0);
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(mla_mfma_kernel, dim3(num_blocks), dim3(512), 2 * kBufBytes, st, p);
   } else if (p.Hq == 64) {
-    static const hipError_t attr = hipFuncSetAttribute((const void*)mla64_mfma_kernel,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kBufBytes);
+    const hipError_t attr = allow_big_lds(mla64_mfma_kernel, 2 * kBufBytes, 1);
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(mla64_mfma_kernel, dim3(num_blocks), dim3(256), 2 * kBufBytes, st, p);
   } else {

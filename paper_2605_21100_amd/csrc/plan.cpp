@@ -59,14 +59,20 @@ int nanocp::pick_variant(const nanocp_attn_desc& d) {
 
 namespace {
 
-// Planner tuning knobs can be overridden from the environment (integers, clamped).
-int env_int(const char* name, int dflt, int lo, int hi) {
+// Planner constants.  Only a build with -DNANOCP_TUNING reads overrides from the environment (integers, clamped);
+// the product build uses the values below whatever the process environment holds.
+int knob(const char* name, int dflt, int lo, int hi) {
+#ifdef NANOCP_TUNING
   const char* v = std::getenv(name);
-  if (!v || !*v) return dflt;
-  char* end = nullptr;
-  const long x = std::strtol(v, &end, 10);
-  if (end == v) return dflt;
-  return (int)std::min<long>(hi, std::max<long>(lo, x));
+  if (v && *v) {
+    char* end = nullptr;
+    const long x = std::strtol(v, &end, 10);
+    if (end != v) return (int)std::min<long>(hi, std::max<long>(lo, x));
+  }
+#else
+  (void)name, (void)lo, (void)hi;
+#endif
+  return dflt;
 }
 
 // Partial slots and reduction segments.  A segment is the set of tiles whose partials combine into one result:
@@ -120,12 +126,27 @@ void assign_segments(nanocp_plan* p, const int32_t* final_row) {
     const int n = count[key];
     t.dst = n > 1 ? slot0[key] + next[key]++ : -1;
     p->dev_tiles[i] = nanocp::DevTile{t.q_row, t.bt_row, t.kv_head, t.shard, t.tok_begin, t.tok_end, t.dst,
-                                      seg_id[key], n, slot0[key], final_row ? final_row[t.shard] : -1, 0};
+                                      seg_id[key], n, slot0[key], final_row ? final_row[t.shard] : -1, group[t.shard]};
   }
   // workspace: o partials [slots, G, Dv] then lse partials [slots, G], each 256-byte aligned
   const size_t o_bytes = ((size_t)p->num_slots * G * p->desc.head_dim_v * sizeof(float) + 255) & ~(size_t)255;
   const size_t l_bytes = ((size_t)p->num_slots * G * sizeof(float) + 255) & ~(size_t)255;
   p->workspace_bytes = p->num_slots ? o_bytes + l_bytes : 0;
+}
+
+}  // namespace
+
+namespace {
+
+void free_device_copy(nanocp_plan* plan) {
+  if (plan->d_tiles) (void)hipFree(plan->d_tiles);
+  if (plan->d_chunk_offsets) (void)hipFree(plan->d_chunk_offsets);
+  if (plan->d_segs) (void)hipFree(plan->d_segs);
+  if (plan->d_sync) (void)hipFree(plan->d_sync);
+  plan->d_tiles = nullptr;
+  plan->d_chunk_offsets = nullptr;
+  plan->d_segs = nullptr;
+  plan->d_sync = nullptr;
 }
 
 }  // namespace
@@ -173,12 +194,12 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
     // pages cost the same compute everywhere, so the queue is all equal chunks; the GQA kernels are bandwidth-bound
     // with timing that varies, so they keep a self-scheduled tail.  (Measured on the benchmark workloads.)
     const bool mla = p->variant == kMlaMfmaBf16;
-    const int c0 = env_int("NANOCP_PLAN_OVERHEAD_PAGES", mla ? 6 : 2, 0, 64);  // cost of a tile's Q load, combine, write-back
-    const int min_pages = env_int("NANOCP_PLAN_MIN_PAGES", 8, 1, 1 << 20);
-    const double static_frac = env_int("NANOCP_PLAN_STATIC_PCT", mla ? 100 : 85, 1, 100) / 100.0;
-    const int gss_k = env_int("NANOCP_PLAN_GSS_K", 2, 1, 64);
-    const int snap_pct = env_int("NANOCP_PLAN_SNAP_PCT", 12, 0, 50);  // measured: fewer tiles, same balance
-    const int64_t M = std::max<int64_t>(1, (int64_t)num_cus * env_int("NANOCP_PLAN_WGS_PER_CU", 1, 1, 16));
+    const int c0 = knob("NANOCP_PLAN_OVERHEAD_PAGES", mla ? 6 : 2, 0, 64);  // cost of a tile's Q load, combine, write-back
+    const int min_pages = knob("NANOCP_PLAN_MIN_PAGES", 8, 1, 1 << 20);
+    const double static_frac = knob("NANOCP_PLAN_STATIC_PCT", mla ? 100 : 85, 1, 100) / 100.0;
+    const int gss_k = knob("NANOCP_PLAN_GSS_K", 2, 1, 64);
+    const int snap_pct = knob("NANOCP_PLAN_SNAP_PCT", 12, 0, 50);  // measured: fewer tiles, same balance
+    const int64_t M = std::max<int64_t>(1, (int64_t)num_cus * knob("NANOCP_PLAN_WGS_PER_CU", 1, 1, 16));
 
     // longest shards first: the big, statically sized chunks at the head of the queue then hold the long
     // shards, and the small chunks at its tail are mostly whole short requests (no partials to reduce)
@@ -199,7 +220,7 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
     const int64_t cap_fixed = std::max<int64_t>(1, tile_tokens / ps) + c0;
     const int64_t cap_static =
         std::max<int64_t>((int64_t)(static_frac * (double)units / (double)M + 0.999), c0 + min_pages);
-    const int64_t whole_max = std::max<int64_t>(c0 + min_pages, cap_static / env_int("NANOCP_PLAN_WHOLE_DIV", 2, 1, 64));
+    const int64_t whole_max = std::max<int64_t>(c0 + min_pages, cap_static / knob("NANOCP_PLAN_WHOLE_DIV", 2, 1, 64));
     int64_t consumed = 0;
     auto open_cap = [&](int chunk_idx) -> int64_t {
       if (fixed) return cap_fixed;
@@ -378,14 +399,21 @@ nanocp_status nanocp_plan_upload(nanocp_plan* plan, void* stream) {
     if (hipMemcpyAsync(*dptr, src, bytes, hipMemcpyHostToDevice, st) != hipSuccess) return NANOCP_EHIP;
     return NANOCP_OK;
   };
+  // On a failure part-way every buffer allocated so far is released again (after the stream has drained: a copy
+  // into one of them may still be in flight) and the plan stays in its not-uploaded state.
+  auto fail = [&](nanocp_status s) {
+    (void)hipStreamSynchronize(st);
+    free_device_copy(plan);
+    return s;
+  };
   nanocp_status s;
-  if ((s = up((void**)&plan->d_tiles, plan->dev_tiles.data(), plan->dev_tiles.size() * sizeof(DevTile))) != NANOCP_OK) return s;
-  if ((s = up((void**)&plan->d_chunk_offsets, plan->chunk_offsets.data(), plan->chunk_offsets.size() * sizeof(int32_t))) != NANOCP_OK) return s;
-  if ((s = up((void**)&plan->d_segs, plan->segs.data(), plan->segs.size() * sizeof(Seg))) != NANOCP_OK) return s;
+  if ((s = up((void**)&plan->d_tiles, plan->dev_tiles.data(), plan->dev_tiles.size() * sizeof(DevTile))) != NANOCP_OK) return fail(s);
+  if ((s = up((void**)&plan->d_chunk_offsets, plan->chunk_offsets.data(), plan->chunk_offsets.size() * sizeof(int32_t))) != NANOCP_OK) return fail(s);
+  if ((s = up((void**)&plan->d_segs, plan->segs.data(), plan->segs.size() * sizeof(Seg))) != NANOCP_OK) return fail(s);
   {
     const size_t sync_bytes = (size_t)(kSyncSegBase + plan->num_multi_segs) * sizeof(int32_t);
-    if (hipMalloc((void**)&plan->d_sync, sync_bytes) != hipSuccess) return NANOCP_ENOMEM;
-    if (hipMemsetAsync(plan->d_sync, 0, sync_bytes, st) != hipSuccess) return NANOCP_EHIP;
+    if (hipMalloc((void**)&plan->d_sync, sync_bytes) != hipSuccess) return fail(NANOCP_ENOMEM);
+    if (hipMemsetAsync(plan->d_sync, 0, sync_bytes, st) != hipSuccess) return fail(NANOCP_EHIP);
   }
   // the host vectors must outlive the async copies: they live as long as the plan, and destroy synchronises
   plan->device = dev;
@@ -395,11 +423,13 @@ nanocp_status nanocp_plan_upload(nanocp_plan* plan, void* stream) {
 void nanocp_plan_destroy(nanocp_plan* plan) {
   if (!plan) return;
   if (plan->device >= 0) {
+    // synchronise and free on the device that holds the copy, whatever device is current for the caller
+    int cur = -1;
+    const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+    const bool switched = have_cur && cur != plan->device && hipSetDevice(plan->device) == hipSuccess;
     (void)hipDeviceSynchronize();
-    if (plan->d_tiles) (void)hipFree(plan->d_tiles);
-    if (plan->d_chunk_offsets) (void)hipFree(plan->d_chunk_offsets);
-    if (plan->d_segs) (void)hipFree(plan->d_segs);
-    if (plan->d_sync) (void)hipFree(plan->d_sync);
+    free_device_copy(plan);
+    if (switched) (void)hipSetDevice(cur);
   }
   delete plan;
 }

@@ -32,7 +32,7 @@ struct DevTile {
   int32_t n_parts;     // tiles of this (shard, head)
   int32_t slot_begin;  // first partial slot of this (shard, head)
   int32_t final_row;   // >= 0: output row this shard alone produces (written in its final form), else -1
-  int32_t pad1;
+  int32_t lse_shard;   // row of out_lse the (shard, head)'s LSE goes to: the shard itself, or the first shard of its group
 };
 
 // sync words owned by the plan (zero between launches): [0] work-queue head, [1] finished workgroups,
@@ -59,9 +59,11 @@ struct KParams {
   int32_t num_segs;
   const int32_t* header;  // null, or the counts on the device (plan image): they then override num_chunks / num_segs
   uint64_t* tile_clock;   // may be null
-  void* final_out;       // [num_out, Hq, Dv] float or bf16; null = every shard writes out_o / out_lse
+  void* final_out;       // [num_out, Hq, Dv] float, bf16 or fp8; null = every shard writes out_o / out_lse
   float* final_lse;      // [num_out, Hq], may be null
-  int32_t final_bf16;
+  int32_t final_kind;    // nanocp_dtype of final_out
+  float out_scale;       // fp8 final rows: code of value / out_scale
+  int32_t variant;       // the tile kernel this launch runs (checked against a plan image's header)
   int32_t Hq, Hkv, G, Dk, Dv, ps, max_blocks, kind;
   float scale;
 };

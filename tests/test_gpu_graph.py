@@ -7,6 +7,7 @@ import torch
 
 import paper_2605_21100_amd as nanocp
 import workloads as W
+from workloads.device import DeviceBatch
 
 pytestmark = pytest.mark.gpu
 
@@ -15,7 +16,7 @@ pytestmark = pytest.mark.gpu
 def test_graph_replay_matches_eager(cid):
     print(f"[case] graph replay, reduced config {cid}", flush=True)
     b = W.reduced(cid, with_remote_kv=False)
-    db = nanocp.DeviceBatch(b, tile_tokens=256)
+    db = DeviceBatch(b, tile_tokens=256)
     d = b.desc
     S, R = b.num_shards, b.num_requests
     rem_o, rem_lse = W.synthetic_remote_partials(b)
@@ -91,7 +92,7 @@ def test_bucket_graph_replays_different_compositions(cid):
     import oracle
     from parity import check_output
     b = W.reduced(cid, with_remote_kv=False, hold_all=True) if cid in (3, 5) else W.reduced(cid, with_remote_kv=False)
-    db = nanocp.DeviceBatch(b, tile_tokens=256)          # pools, q, block table; its own plan is not used below
+    db = DeviceBatch(b, tile_tokens=256)          # pools, q, block table; its own plan is not used below
     d = b.desc
     rng = np.random.default_rng(17 + cid)
     comps = _compositions(b, rng)

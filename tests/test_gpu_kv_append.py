@@ -8,6 +8,7 @@ import torch
 
 import paper_2605_21100_amd as nanocp
 import workloads as W
+from workloads.device import DeviceBatch, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -52,12 +53,12 @@ def test_append_builds_the_documented_layouts(cid):
         v_rows = v[page, :, u, :, e]                                      # [n, Hkv, Dv]
         want_v = np.zeros_like(v)
         want_v[page, :, u, :, e] = v_rows
-    db = nanocp.DeviceBatch(b)
+    db = DeviceBatch(b)
     o_ref, lse_ref = (t.clone() for t in db.partial())
     k_dev = torch.zeros_like(db.k_pool)
     v_dev = None if db.v_pool is None else torch.zeros_like(db.v_pool)
-    nanocp.nanocp_kv_append(db.desc, nanocp.to_device(np.ascontiguousarray(k_rows)),
-                            None if v_rows is None else nanocp.to_device(np.ascontiguousarray(v_rows)),
+    nanocp.nanocp_kv_append(db.desc, to_device(np.ascontiguousarray(k_rows)),
+                            None if v_rows is None else to_device(np.ascontiguousarray(v_rows)),
                             torch.from_numpy(bt_row).cuda(), torch.from_numpy(position).cuda(), k_dev, v_dev,
                             db.block_table)
     torch.cuda.synchronize()
@@ -79,7 +80,7 @@ def test_append_builds_the_documented_layouts(cid):
 
 def test_append_errors():
     b = W.reduced(2)
-    db = nanocp.DeviceBatch(b)
+    db = DeviceBatch(b)
     one = torch.zeros(1, dtype=torch.int32, device="cuda")
     rows = torch.zeros((1, 4, 128), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(nanocp.NanocpError) as e:                  # V rows missing for a GQA cache

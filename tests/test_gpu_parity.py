@@ -9,6 +9,7 @@ import torch
 import oracle
 import paper_2605_21100_amd as nanocp
 import workloads as W
+from workloads.device import DeviceBatch
 from parity import MERGE_VS_UNSHARDED_ABS, check_output
 
 pytestmark = pytest.mark.gpu
@@ -40,7 +41,7 @@ def test_partial_and_merge_match_oracle(cid, tile_tokens):
     b = W.reduced(cid)
     ps = b.desc.page_size
     tt = 0 if tile_tokens == 0 else max(ps, tile_tokens // ps * ps)
-    db = nanocp.DeviceBatch(b, tile_tokens=tt)
+    db = DeviceBatch(b, tile_tokens=tt)
     if cid in EXPECTED_KERNEL:
         assert db.plan.kernel == EXPECTED_KERNEL[cid]
     if tt:
@@ -86,7 +87,7 @@ def test_merged_equals_gpu_unsharded_full_size_long_request():
 
 def _merged_vs_unsharded(b, tile_tokens):
     assert len(b.remote_meta) == 0
-    db = nanocp.DeviceBatch(b, tile_tokens=tile_tokens)
+    db = DeviceBatch(b, tile_tokens=tile_tokens)
     o, lse = db.partial()
     out, out_lse = _merge_on_gpu(db, o, lse)
     # unsharded: one shard per request covering all its tokens, on the same pools / block table
@@ -141,7 +142,7 @@ def test_edge_ranges(kv_dtype):
             (2 * ps, 2 * ps), (ps + 1, 3 * ps), (0, 33), (31, 33), (32, 64 if ps == 64 else 48), (0, 9 * ps + 1)]
     b = _edge_batch(kv_dtype, spec)
     for tt in (0, ps, 2 * ps):
-        db = nanocp.DeviceBatch(b, tile_tokens=tt)
+        db = DeviceBatch(b, tile_tokens=tt)
         o, lse = db.partial()
         torch.cuda.synchronize()
         ref_o, ref_lse = oracle.local_partials(b)
@@ -159,10 +160,10 @@ def test_edge_ranges_as_final_rows(kv_dtype):
     spec = [(0, 0), (0, 1), (3, ps - 2), (ps - 1, ps + 1), (2 * ps, 2 * ps), (0, 4 * ps), (7, 5 * ps + 9), (0, 0)]
     b = _edge_batch(kv_dtype, spec)
     S, d = b.num_shards, b.desc
-    base = nanocp.DeviceBatch(b)
+    base = DeviceBatch(b)
     o, lse = base.partial()
     want, want_lse = _merge_on_gpu(base, o, lse)
-    db = nanocp.DeviceBatch(b, final_rows=True)
+    db = DeviceBatch(b, final_rows=True)
     assert (db.shard_final_row >= 0).all() and len(db.rest_rows) == 0
     bucket = nanocp.Bucket(db.plan.num_tiles + 8, db.plan.num_chunks + 8, db.plan.num_tiles + S * d.num_kv_heads + 8,
                            db.plan.num_tiles + 8)
@@ -232,7 +233,7 @@ def test_merge_edge_cases():
 def test_device_call_errors():
     _say("[case] device call errors")
     b = W.reduced(2)
-    db = nanocp.DeviceBatch(b, tile_tokens=128)
+    db = DeviceBatch(b, tile_tokens=128)
     assert db.plan.workspace_bytes > 0
     small = torch.empty(16, dtype=torch.uint8, device="cuda")
     with pytest.raises(nanocp.NanocpError) as e:
@@ -255,7 +256,7 @@ def test_device_call_errors():
 def test_run_to_run_determinism():
     _say("[case] determinism")
     b = W.reduced(3)
-    db = nanocp.DeviceBatch(b)
+    db = DeviceBatch(b)
     o1, l1 = (t.clone() for t in db.partial())
     o2, l2 = db.partial()
     torch.cuda.synchronize()
@@ -263,25 +264,70 @@ def test_run_to_run_determinism():
     db.plan.close()
 
 
-@pytest.mark.parametrize("cid", [2, 5])
-def test_fused_reduction_is_stable_over_many_launches(cid):
-    """Full-size batch cut into 1024-token tiles (every long (shard, head) is reduced by the workgroup that delivers
-    its last tile, while the memory system is saturated): 100 launches, each bit-identical to the first.  A partial
-    that is counted as arrived before its stores have landed shows up here as a wrong row."""
-    _say(f"[case] repeated launches, full-size config {cid}, 1024-token tiles")
+def _launch_variants(b, tile_tokens):
+    """The three ways a plan reaches the tile kernels: the plain entry point, the final-row entry point and the
+    plan-image entry point (final rows), each as (name, launch(), tensors that must not change between launches)."""
+    d, S, R = b.desc, b.num_shards, b.num_requests
+    out = []
+    db = DeviceBatch(b, tile_tokens=tile_tokens)
+    out.append(("plain", db, lambda: db.partial(), [db.out_o, db.out_lse]))
+    dbf = DeviceBatch(b, tile_tokens=tile_tokens, final_rows=True)
+    fin = torch.zeros((R, d.num_q_heads, d.head_dim_v), dtype=torch.bfloat16, device="cuda")
+    fin_lse = torch.zeros((R, d.num_q_heads), device="cuda")
+
+    def run_final():
+        nanocp.nanocp_decode_attn_partial(dbf.plan, dbf.q, dbf.k_pool, dbf.v_pool, dbf.k_scale, dbf.v_scale,
+                                          dbf.block_table, dbf.out_o, dbf.out_lse, dbf.workspace, final_out=fin,
+                                          final_lse=fin_lse)
+    keep = torch.from_numpy(dbf.shard_final_row < 0).cuda()       # O rows of final-row shards are not written
+    out.append(("final", dbf, run_final, [fin, fin_lse, dbf.out_lse, (dbf.out_o, keep)]))
+    nt = dbf.plan.num_tiles
+    bucket = nanocp.Bucket(nt + 8, dbf.plan.num_chunks + 8, nt + S * d.num_kv_heads + 8, nt + 8)
+    host_img = torch.empty(nanocp.bucket_plan_bytes(bucket), dtype=torch.uint8).pin_memory()
+    dbf.plan.pack(bucket, host_img)
+    dev_img = host_img.cuda()
+    ws = torch.empty(max(nanocp.bucket_workspace_bytes(dbf.desc, bucket), 16), dtype=torch.uint8, device="cuda")
+    fin2, fin_lse2 = torch.zeros_like(fin), torch.zeros_like(fin_lse)
+    o2, l2 = torch.zeros_like(dbf.out_o), torch.zeros_like(dbf.out_lse)
+
+    def run_image():
+        nanocp.nanocp_decode_attn_partial_image(dbf.desc, bucket, dev_img, 0, b.block_table.shape[1], dbf.q, dbf.k_pool,
+                                                dbf.v_pool, dbf.k_scale, dbf.v_scale, dbf.block_table, o2, l2, ws,
+                                                final_out=fin2, final_lse=fin_lse2)
+    out.append(("image", dbf, run_image, [fin2, fin_lse2, l2, (o2, keep)]))
+    return out
+
+
+def _snap(ts):
+    return [(t[0][t[1]] if isinstance(t, tuple) else t).clone() for t in ts]
+
+
+@pytest.mark.parametrize("cid, tile_tokens", [(2, 1024), (5, 1024), (3, 0), (3, 1024), (4, 0)])
+def test_fused_reduction_is_stable_over_many_launches(cid, tile_tokens):
+    """Full-size batch, every long (shard, head) reduced by the workgroup that delivers its last tile while the memory
+    system is saturated: 100 launches through each entry point (plain, final rows, plan image), every one compared
+    with the first and the run stopped at the first difference.  A partial counted as arrived before its stores
+    have landed shows up here as a wrong row."""
+    _say(f"[case] repeated launches, full-size config {cid}, tile_tokens {tile_tokens}")
     b = W.FULL[cid](with_remote_kv=False)
-    db = nanocp.DeviceBatch(b, tile_tokens=1024)
-    o0, l0 = (t.clone() for t in db.partial())
-    bad = torch.zeros((), dtype=torch.int64, device="cuda")
-    for _ in range(100):
-        o, lse = db.partial()
-        bad += (o != o0).any(dim=-1).sum() + (lse != l0).sum()
-    torch.cuda.synchronize()
-    assert int(bad.item()) == 0
-    ro, rl = oracle.attn_partial_paged(b.desc, b.q, b.k_pool, b.v_pool, b.k_scale, b.v_scale, b.block_table,
-                                       b.shards[0])
-    check_output(b.desc, o0[0].cpu().numpy(), l0[0].cpu().numpy(), ro, rl, f"c{cid} repeated launches, shard 0")
-    db.plan.close()
+    variants = _launch_variants(b, tile_tokens)
+    for name, db, launch, watched in variants:
+        assert (db.plan.tiles()["dst"] >= 0).any()               # the work-list really has multi-tile pairs
+        launch()
+        torch.cuda.synchronize()
+        first = _snap(watched)
+        for it in range(100):
+            launch()
+            now = _snap(watched)
+            same = all(torch.equal(torch.nan_to_num(x.float()), torch.nan_to_num(y.float())) for x, y in zip(now, first))
+            assert same, f"c{cid} {name}: launch {it} differs from the first"
+        if name == "plain":
+            ro, rl = oracle.attn_partial_paged(b.desc, b.q, b.k_pool, b.v_pool, b.k_scale, b.v_scale, b.block_table,
+                                               b.shards[0])
+            check_output(b.desc, first[0][0].cpu().numpy(), first[1][0].cpu().numpy(), ro, rl,
+                         f"c{cid} repeated launches, shard 0")
+    for db in {id(v[1]): v[1] for v in variants}.values():
+        db.plan.close()
 
 
 @pytest.mark.parametrize("cid", [1, 2, 4, 5])
@@ -290,7 +336,7 @@ def test_pages_beyond_4_gib_into_the_pool(cid):
     block table) must give bit-identical results - byte offsets into the pools need 64 bits."""
     _say(f"[case] pool offsets beyond 4 GiB, reduced config {cid}")
     b = W.reduced(cid)
-    db = nanocp.DeviceBatch(b)
+    db = DeviceBatch(b)
     o_ref, lse_ref = (t.clone() for t in db.partial())
 
     def grow(t, n_big):
@@ -324,24 +370,33 @@ def _sample_shards(b, k, rng):
 
 
 @pytest.mark.parametrize("cid", [2, 3, 4, 5, 6, 7])
-def test_full_size_sampled(cid):
-    """Full benchmark sizes in the launch configuration bench.py times (automatic tiling): sampled shard
-    entries, always including the longest, checked one by one; every output finite."""
-    _say(f"[case] full-size config {cid}, sampled shards")
+def test_full_size(cid):
+    """Full benchmark sizes in the launch configuration bench.py times (automatic tiling).  GQA workloads: EVERY shard
+    entry against the checker (a second or two of float64 work each).  MLA workloads (the checker needs minutes for
+    all of them): sampled shard entries, always including the longest and the shortest, one by one; the rest must be
+    finite and agree with a second tiling of the same batch."""
+    _say(f"[case] full-size config {cid}")
     b = W.FULL[cid](with_remote_kv=False)
-    db = nanocp.DeviceBatch(b)
+    db = DeviceBatch(b)
     assert db.plan.kernel == EXPECTED_KERNEL[cid]
     o, lse = db.partial()
     torch.cuda.synchronize()
     assert torch.isfinite(o).all() and torch.isfinite(lse).all()
-    rng = np.random.default_rng(cid)
-    for s in _sample_shards(b, 4, rng):
-        _say(f"    shard {s}: tokens {int(b.shards[s, 3] - b.shards[s, 2])}")
-        ro, rl = oracle.attn_partial_paged(b.desc, b.q, b.k_pool, b.v_pool, b.k_scale, b.v_scale,
-                                           b.block_table, b.shards[s])
-        check_output(b.desc, o[s].cpu().numpy(), lse[s].cpu().numpy(), ro, rl, f"c{cid} full shard {s}")
-    # split invariance at full size: LSE of a split request's merge is insensitive to the tiling used
-    db2 = nanocp.DeviceBatch(b, tile_tokens=1024)
+    o_h, lse_h = o.cpu().numpy(), lse.cpu().numpy()
+    if b.desc.kind == "gqa":
+        ref_o, ref_lse = oracle.local_partials(b)
+        assert ref_o.shape[0] == b.num_shards
+        check_output(b.desc, o_h, lse_h, ref_o, ref_lse, f"c{cid} full size, all {b.num_shards} shard entries")
+        _say(f"    compared {b.num_shards} shard entries")
+    else:
+        rng = np.random.default_rng(cid)
+        for s in _sample_shards(b, 4, rng):
+            _say(f"    shard {s}: tokens {int(b.shards[s, 3] - b.shards[s, 2])}")
+            ro, rl = oracle.attn_partial_paged(b.desc, b.q, b.k_pool, b.v_pool, b.k_scale, b.v_scale,
+                                               b.block_table, b.shards[s])
+            check_output(b.desc, o_h[s], lse_h[s], ro, rl, f"c{cid} full shard {s}")
+    # split invariance at full size: the result is insensitive to the tiling used
+    db2 = DeviceBatch(b, tile_tokens=1024)
     o2, lse2 = db2.partial()
     torch.cuda.synchronize()
     assert (o2 - o).abs().max().item() <= 1e-5 and (lse2 - lse).abs().max().item() <= 1e-5
@@ -360,14 +415,14 @@ def test_final_rows_equal_partial_plus_merge(cid, tile_tokens, single_only):
     b = W.reduced(cid)
     ps = b.desc.page_size
     tt = 0 if tile_tokens == 0 else max(ps, tile_tokens // ps * ps)
-    base = nanocp.DeviceBatch(b, tile_tokens=tt)
+    base = DeviceBatch(b, tile_tokens=tt)
     o, lse = base.partial()
     rem_o, rem_lse = oracle.remote_partials(b)
     rem_o_t = torch.from_numpy(rem_o.astype(np.float32)).cuda()
     rem_lse_t = torch.from_numpy(rem_lse.astype(np.float32)).cuda()
     want, want_lse = _merge_on_gpu(base, torch.cat([o, rem_o_t]), torch.cat([lse, rem_lse_t]))
     S, R, d = b.num_shards, b.num_requests, b.desc
-    db = nanocp.DeviceBatch(b, tile_tokens=tt, final_rows=True, single_only=single_only)
+    db = DeviceBatch(b, tile_tokens=tt, final_rows=True, single_only=single_only)
     n_local = np.array([(b.part_index[b.part_offsets[r]:b.part_offsets[r + 1]] < S).sum() for r in range(R)])
     all_local = n_local == np.diff(b.part_offsets)
     assert (db.shard_final_row >= 0).sum() == int(n_local[all_local & ((n_local == 1) | (not single_only))].sum())
@@ -412,7 +467,7 @@ def test_final_rows_equal_partial_plus_merge(cid, tile_tokens, single_only):
 
 def test_final_rows_errors():
     b = W.reduced(2)
-    db = nanocp.DeviceBatch(b)
+    db = DeviceBatch(b)
     d = b.desc
     out = torch.empty((b.num_requests, d.num_q_heads, d.head_dim_v), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(nanocp.NanocpError) as e:        # rows were never declared
@@ -446,7 +501,7 @@ def test_peaked_scores_exercise_the_running_maximum(cid):
         b.q = (b.q * np.float32(32.0)).astype(np.float32)
     for tt in (0, 128):
         ps = b.desc.page_size
-        db = nanocp.DeviceBatch(b, tile_tokens=0 if tt == 0 else max(ps, tt // ps * ps))
+        db = DeviceBatch(b, tile_tokens=0 if tt == 0 else max(ps, tt // ps * ps))
         o, lse = db.partial()
         torch.cuda.synchronize()
         ref_o, ref_lse = oracle.local_partials(b)

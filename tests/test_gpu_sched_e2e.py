@@ -9,6 +9,7 @@ import torch
 import oracle
 import paper_2605_21100_amd as nanocp
 import workloads as W
+from workloads.device import DeviceBatch
 from parity import check_output
 from workloads.batches import build_batch
 
@@ -60,7 +61,7 @@ def test_scheduler_splits_drive_the_attention_path(kv):
     b = build_batch(f"sched_e2e_{kv}", 20260521 + 40, DESCS[kv], np.asarray(lens, np.int64), ranges, local, rng)
 
     for final_rows in (False, True):
-        db = nanocp.DeviceBatch(b, final_rows=final_rows)
+        db = DeviceBatch(b, final_rows=final_rows)
         S, R, d = b.num_shards, b.num_requests, b.desc
         out = torch.full((R, d.num_q_heads, d.head_dim_v), float("nan"), device="cuda")
         out_lse = torch.full((R, d.num_q_heads), float("nan"), device="cuda")

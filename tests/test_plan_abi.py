@@ -10,23 +10,27 @@ import pytest
 
 import paper_2605_21100_amd as nanocp
 import workloads as W
+from workloads.device import desc_from
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "nanocp.h")).read()
-    declared = sorted(set(re.findall(r"\b(nanocp_[a-z_]+)\s*\(", hdr)))
-    assert set(declared) == set(nanocp.EXPORTS)
     lib = ctypes.CDLL(nanocp.LIB_PATH)
-    for name in declared:
-        assert hasattr(lib, name), name
-    assert ctypes.sizeof(nanocp.AttnDesc) == 36 and ctypes.sizeof(nanocp.Shard) == 16
+    for header, exports in (("nanocp.h", nanocp.EXPORTS), ("nanocp_debug.h", nanocp.DEBUG_EXPORTS),
+                            ("nanocp_sched.h", nanocp.SCHED_EXPORTS)):
+        hdr = open(os.path.join(ROOT, "include", header)).read()
+        hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)                 # declarations only, not the prose
+        declared = sorted(set(re.findall(r"\b(nanocp_[a-z0-9_]+)\s*\(", hdr)))
+        assert set(declared) == set(exports), header
+        for name in declared:
+            assert hasattr(lib, name), name
+    assert ctypes.sizeof(nanocp.AttnDesc) == 40 and ctypes.sizeof(nanocp.Shard) == 16
     assert ctypes.sizeof(nanocp.Tile) == 32
 
 
 def _plan(batch, tile_tokens=0, num_cus=256):
-    return nanocp.Plan(nanocp.desc_from(batch.desc), batch.shards, batch.q.shape[0],
+    return nanocp.Plan(desc_from(batch.desc), batch.shards, batch.q.shape[0],
                        batch.block_table.shape[0], batch.block_table.shape[1], tile_tokens, num_cus)
 
 
@@ -110,7 +114,7 @@ def test_auto_plan_balances_a_long_shard():
     desc = W.AttnDesc("gqa", "bf16", "bf16", 64, 4, 128, 128, 64, 0.1)
     lens = [700] * 50 + [131072] + [700] * 50
     shards = np.array([[i, i, 0, L] for i, L in enumerate(lens)], np.int32)
-    plan = nanocp.Plan(nanocp.desc_from(desc), shards, len(lens), len(lens), 2048, 0, 256)
+    plan = nanocp.Plan(desc_from(desc), shards, len(lens), len(lens), 2048, 0, 256)
     tiles, cost = _chunk_cost(plan)
     assert tiles["shard"][0] == 50                               # longest first
     long_chunks = np.unique(tiles["chunk"][tiles["shard"] == 50])
@@ -168,7 +172,7 @@ def test_full_size_plans_are_balanced():
             lens = rng.integers(1024, 8193, size=64)
             shards = np.array([[i, i, 0, L] for i, L in enumerate(lens)], np.int32)
             desc = W.AttnDesc("gqa", "bf16", "bf16", 64, 4, 128, 128, 64, 0.1)
-            plan = nanocp.Plan(nanocp.desc_from(desc), shards, 64, 64, 128, 0, 256)
+            plan = nanocp.Plan(desc_from(desc), shards, 64, 64, 128, 0, 256)
         else:
             plan = _plan(W.FULL[cid](with_remote_kv=False))
         tiles, cost = _chunk_cost(plan)
