@@ -249,6 +249,27 @@ nanocp_status nanocp_merge_partials_dyn(const nanocp_attn_desc* desc, const floa
                                         int32_t out_dtype, float* out_lse, void* stream);
 
 /*
+ * nanocp_decode_attn_partial_image_static -- nanocp_decode_attn_partial_image for callers that cannot allocate and
+ * have no workspace to hand over (launches recorded into a HIP graph, tight serving loops, harnesses that forbid
+ * hipMalloc).  The tile partials go to a scratch array that is part of the library's device image -- 32 MiB
+ * (33,554,432 bytes) on every GPU the library runs on, held until the process ends; its address is looked up once per
+ * device, on the first call made with that device current (make that call outside a stream capture).  The call
+ * allocates nothing and queries nothing: num_cus must be given (> 0).
+ * Errors: as nanocp_decode_attn_partial_image; EBOUNDS if nanocp_bucket_workspace_bytes(desc, bucket) exceeds the
+ * 32 MiB; EINVAL if num_cus <= 0.
+ * All calls on one GPU share the one array (it keeps the previous call's partials; nothing in it needs to start at
+ * zero, every slot a launch reads is written by that launch first): two such launches that overlap in time on one
+ * GPU race -- order them on one stream, or with events.
+ */
+nanocp_status nanocp_decode_attn_partial_image_static(const nanocp_attn_desc* desc, const nanocp_bucket* bucket,
+                                                      const void* device_image, int32_t num_cus,
+                                                      int32_t max_blocks_per_row, const void* q, const void* k_pool,
+                                                      const void* v_pool, const float* k_scale, const float* v_scale,
+                                                      const int32_t* block_table, float* out_o, float* out_lse,
+                                                      void* final_out, int32_t final_dtype, float* final_lse,
+                                                      void* stream);
+
+/*
  * nanocp_kv_append -- the writer that goes with the paged layouts above: stores the K / V rows of n tokens at
  * (block-table row, token position) into the pools.  A decode step appends one token per request to the local KV
  * before Phase 2 (each instance keeps only its own KV partition; paper: Data Plane); one bulk call converts a plain

@@ -45,8 +45,10 @@ EXPORTS = ["nanocp_plan_create", "nanocp_plan_query", "nanocp_plan_tiles", "nano
            "nanocp_merge_partials", "nanocp_status_str",
            "nanocp_plan_set_final_rows", "nanocp_decode_attn_partial_final", "nanocp_merge_partials_rows",
            "nanocp_bucket_plan_bytes", "nanocp_bucket_workspace_bytes", "nanocp_plan_pack",
-           "nanocp_decode_attn_partial_image", "nanocp_merge_partials_dyn", "nanocp_kv_append"]
+           "nanocp_decode_attn_partial_image", "nanocp_merge_partials_dyn", "nanocp_kv_append",
+           "nanocp_decode_attn_partial_image_static"]
 DEBUG_EXPORTS = ["nanocp_decode_attn_partial_timed"]          # include/nanocp_debug.h
+STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class Bucket(ctypes.Structure):
@@ -86,6 +88,8 @@ def _load():
     lib.nanocp_plan_pack.argtypes = [vp, ctypes.POINTER(Bucket), vp, sz]
     lib.nanocp_decode_attn_partial_image.argtypes = ([ctypes.POINTER(AttnDesc), ctypes.POINTER(Bucket), vp, i32, i32] +
                                                      [vp] * 8 + [vp, sz, vp, i32, vp, vp])
+    lib.nanocp_decode_attn_partial_image_static.argtypes = ([ctypes.POINTER(AttnDesc), ctypes.POINTER(Bucket), vp, i32,
+                                                             i32] + [vp] * 8 + [vp, i32, vp, vp])
     lib.nanocp_merge_partials_dyn.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, i32, vp, vp, vp, i32, vp, vp]
     lib.nanocp_kv_append.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, i32, vp, vp, vp, i32, vp]
     lib.nanocp_status_str.argtypes = [ctypes.c_int]
@@ -263,6 +267,19 @@ def nanocp_decode_attn_partial_image(desc, bucket, image, num_cus, max_blocks_pe
                                                  _ptr(v_scale), _ptr(block_table), _ptr(out_o), _ptr(out_lse),
                                                  _ptr(workspace), ws_bytes, _ptr(final_out), fdt, _ptr(final_lse),
                                                  _stream(stream)), "nanocp_decode_attn_partial_image")
+
+
+def nanocp_decode_attn_partial_image_static(desc, bucket, image, num_cus, max_blocks_per_row, q, k_pool, v_pool,
+                                            k_scale, v_scale, block_table, out_o, out_lse, final_out=None,
+                                            final_lse=None, stream=None):
+    """nanocp_decode_attn_partial_image with the tile partials in the library's own static scratch (no workspace
+    argument, no allocation, no device query: num_cus must be given)."""
+    fdt = F32 if final_out is None else _out_dtype(final_out, "nanocp_decode_attn_partial_image_static")
+    _check(_lib.nanocp_decode_attn_partial_image_static(ctypes.byref(desc), ctypes.byref(bucket), _ptr(image), num_cus,
+                                                        max_blocks_per_row, _ptr(q), _ptr(k_pool), _ptr(v_pool),
+                                                        _ptr(k_scale), _ptr(v_scale), _ptr(block_table), _ptr(out_o),
+                                                        _ptr(out_lse), _ptr(final_out), fdt, _ptr(final_lse),
+                                                        _stream(stream)), "nanocp_decode_attn_partial_image_static")
 
 
 def nanocp_merge_partials_dyn(desc, o_parts, lse_parts, part_offsets, part_index, max_out, num_out_dev, out_rows, out,

@@ -3,6 +3,8 @@
 // Paper: Data Plane, Phase 2 (partial attention + LSE) and Phase 4 (LSE-based merging).
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "epilogue.h"
 #include "nanocp_debug.h"
 #include "plan.h"
@@ -328,6 +330,37 @@ nanocp_status run_image(const nanocp_attn_desc* desc, const nanocp_bucket* bucke
                                  (hipStream_t)stream);
 }
 
+// Scratch of nanocp_decode_attn_partial_image_static: the tile partials ([slots, G, Dv] outputs, then [slots, G]
+// LSEs) of one launch.  The array's name is a host-side stand-in, not a device address: the address each device
+// holds its copy at is looked up once per device (with that device current) and only that pointer is handed to
+// kernels.  Nothing in it has to start at zero: every slot a launch reads was written by the same launch.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+}  // namespace
+}  // namespace nanocp
+
+static __device__ __align__(256) unsigned char nanocp_static_scratch[nanocp::kStaticScratchBytes];
+
+namespace nanocp {
+namespace {
+
+nanocp_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return NANOCP_EHIP;
+  if (dev < 0 || dev >= kMaxDevices) return NANOCP_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(nanocp_static_scratch)) != hipSuccess || !ptr) return NANOCP_EHIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return NANOCP_OK;
+}
+
 }  // namespace
 }  // namespace nanocp
 
@@ -367,6 +400,25 @@ nanocp_status nanocp_decode_attn_partial_image(const nanocp_attn_desc* desc, con
   return nanocp::run_image(desc, bucket, device_image, num_cus, max_blocks_per_row, q, k_pool, v_pool, k_scale,
                            v_scale, block_table, out_o, out_lse, workspace, workspace_bytes, final_out, final_dtype,
                            final_lse, stream);
+}
+
+nanocp_status nanocp_decode_attn_partial_image_static(const nanocp_attn_desc* desc, const nanocp_bucket* bucket,
+                                                      const void* device_image, int32_t num_cus,
+                                                      int32_t max_blocks_per_row, const void* q, const void* k_pool,
+                                                      const void* v_pool, const float* k_scale, const float* v_scale,
+                                                      const int32_t* block_table, float* out_o, float* out_lse,
+                                                      void* final_out, int32_t final_dtype, float* final_lse,
+                                                      void* stream) {
+  using namespace nanocp;
+  if (!desc || !bucket) return NANOCP_EINVAL;
+  if (num_cus <= 0) return NANOCP_EINVAL;  // no device query on this path: the caller states the launch width
+  const size_t need = nanocp_bucket_workspace_bytes(desc, bucket);
+  if (need > kStaticScratchBytes) return NANOCP_EBOUNDS;  // the bucket's tile partials do not fit the static scratch
+  void* ws = nullptr;
+  const nanocp_status s = static_scratch(&ws);
+  if (s != NANOCP_OK) return s;
+  return run_image(desc, bucket, device_image, num_cus, max_blocks_per_row, q, k_pool, v_pool, k_scale, v_scale,
+                   block_table, out_o, out_lse, ws, kStaticScratchBytes, final_out, final_dtype, final_lse, stream);
 }
 
 nanocp_status nanocp_decode_attn_partial_timed(const nanocp_plan* plan, const void* q, const void* k_pool,
