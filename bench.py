@@ -40,19 +40,22 @@ WORKLOAD_NAMES = {1: "config1: tiny fp32 GQA", 2: "config2: bf16 GQA 64 local re
                   7: "config7: config 4's recipe with 64 query heads (MLA-absorbed bf16, 576/512)"}
 
 
-def cpu_baseline(batch, budget_s=20.0):
-    """Time the float64 checker (as it stands) on a bounded sample of the same workload's shard entries."""
-    import oracle
+def _cpu_model():
     try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = 1
-    lens = batch.shards[:, 3] - batch.shards[:, 2]
-    order = np.argsort(-lens)            # longest first: the sample keeps the workload's long tail
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def _oracle_pass(batch, order, lens, budget_s):
+    """Run the float64 checker over shard entries (longest first, repeated) for about budget_s seconds."""
+    import oracle
     done_tokens, picked, passes = 0, 0, 0
     t0 = time.perf_counter()
-    while time.perf_counter() - t0 < budget_s / 2:           # repeat the pass until about 10 s have been spent
+    while time.perf_counter() - t0 < budget_s / 2:           # repeat the pass until about half the budget is spent
         for s in order:
             oracle.attn_partial_paged(batch.desc, batch.q, batch.k_pool, batch.v_pool, batch.k_scale, batch.v_scale,
                                       batch.block_table, batch.shards[s])
@@ -61,11 +64,91 @@ def cpu_baseline(batch, budget_s=20.0):
             if time.perf_counter() - t0 > budget_s:
                 break
         passes += 1
-    dt = time.perf_counter() - t0
-    done_bytes = done_tokens * batch.desc.kv_bytes_per_token
-    return {"value": done_bytes / dt / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+    return done_tokens, picked, passes, time.perf_counter() - t0
+
+
+def cpu_baseline(batch, budget_s=12.0):
+    """Time the float64 checker (as it stands) on a bounded sample of the same workload's shard entries: once with the
+    threads numpy's BLAS takes by itself (all host cores of the box's share), once limited to one thread."""
+    from threadpoolctl import threadpool_info, threadpool_limits
+    cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    lens = batch.shards[:, 3] - batch.shards[:, 2]
+    order = np.argsort(-lens)            # longest first: the sample keeps the workload's long tail
+    bpt = batch.desc.kv_bytes_per_token
+    tok, picked, passes, dt = _oracle_pass(batch, order, lens, budget_s)
+    with threadpool_limits(limits=1):
+        tok1, picked1, passes1, dt1 = _oracle_pass(batch, order, lens, budget_s)
+    return {"value": tok * bpt / dt / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+            "single_thread": {"value": tok1 * bpt / dt1 / 1e9, "unit": "GB/s", "cores": 1,
+                              "sample": f"{picked1} shard entries, longest first, in {passes1} pass(es) "
+                                        f"({tok1} tokens, {dt1:.1f} s)"},
+            "cpu_model": _cpu_model(), "host_cpus_visible": os.cpu_count(),
             "sample": f"{picked} shard entries, longest first, in {passes} pass(es) over the {len(lens)} entries of the "
-                      f"workload ({done_tokens} tokens, {dt:.1f} s), float64 numpy partial attention"}
+                      f"workload ({tok} tokens, {dt:.1f} s), float64 numpy partial attention"}
+
+
+def quick_config(cid, steps, warmup):
+    """One workload's step time and event-timed attention launch, in the default launch configuration (automatic
+    tiling, final rows from the kernel, two pool copies alternated).  Used for the per-config table."""
+    import torch
+    import paper_2605_21100_amd as nanocp
+    import workloads as W
+    from workloads.device import DeviceBatch
+    batch = W.FULL[cid](with_remote_kv=False)
+    d = batch.desc
+    db = DeviceBatch(batch, final_rows=True)
+    pools = [(db.k_pool, db.v_pool, db.k_scale, db.v_scale)]
+    pools.append(tuple(None if t is None else t.clone() for t in pools[0]))
+    S, R = batch.num_shards, batch.num_requests
+    rem_o, rem_lse = W.synthetic_remote_partials(batch)
+    n_rem = rem_o.shape[0]
+    parts_o = torch.empty((S + n_rem, d.num_q_heads, d.head_dim_v), dtype=torch.float32, device="cuda")
+    parts_lse = torch.empty((S + n_rem, d.num_q_heads), dtype=torch.float32, device="cuda")
+    if n_rem:
+        parts_o[S:] = torch.from_numpy(rem_o).cuda()
+        parts_lse[S:] = torch.from_numpy(rem_lse).cuda()
+    out = torch.empty((R, d.num_q_heads, d.head_dim_v), dtype=torch.bfloat16, device="cuda")
+    n_rest = len(db.rest_rows)
+    rest_offsets, rest_index = torch.from_numpy(db.rest_offsets).cuda(), torch.from_numpy(db.rest_index).cuda()
+    rest_rows = torch.from_numpy(db.rest_rows).cuda()
+
+    def step(i, ev=None):
+        k, v, ks, vs = pools[i & 1]
+        if ev:
+            ev[0].record()
+        nanocp.nanocp_decode_attn_partial(db.plan, db.q, k, v, ks, vs, db.block_table, parts_o[:S], parts_lse[:S],
+                                          db.workspace, final_out=out)
+        if ev:
+            ev[1].record()
+        if n_rest:
+            nanocp.nanocp_merge_partials(db.desc, parts_o, parts_lse, rest_offsets, rest_index, n_rest, out,
+                                         out_rows=rest_rows)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / steps * 1e6
+    n_ev = min(steps, 100)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
+    for i in range(n_ev):
+        step(i, evs[i])
+    torch.cuda.synchronize()
+    launch_us = float(np.mean([a.elapsed_time(b) for a, b in evs]) * 1e3)
+    res = {"workload": WORKLOAD_NAMES[cid].format(n=3), "kernel": db.plan.kernel, "kv_bytes": int(batch.kv_bytes),
+           "us_per_step": us, "kv_GBs": batch.kv_bytes / us / 1e3, "pct_of_hbm_peak": batch.kv_bytes / us / 1e3 / 80.0,
+           "launch_us_mean": launch_us, "frac": batch.kv_bytes / launch_us / 1e3 / HBM_PEAK_GBS,
+           "tiles": int(db.plan.num_tiles), "rows_merged": int(n_rest)}
+    if d.kind == "mla":
+        flops = 2.0 * (d.head_dim_qk + d.head_dim_v) * d.num_q_heads * batch.local_tokens
+        res["mfma_frac"] = flops / (launch_us * 1e-6) / 1e12 / 2500.0
+    db.plan.close()
+    del db, pools, parts_o, parts_lse, out
+    torch.cuda.empty_cache()
+    return res
 
 
 def main():
@@ -87,6 +170,8 @@ def main():
     ap.add_argument("--inject-once", action="store_true",
                     help="with --graph: inject the plan image once instead of before every step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the per_config table (step time and event-timed launch of the other workloads)")
     ap.add_argument("--no-straggle", action="store_true")
     ap.add_argument("--dump-tiles", default="", help="write the tile list and per-tile device clocks to this .npz")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -104,6 +189,7 @@ def main():
     from workloads.device import DeviceBatch
 
     torch.cuda.set_device(0)
+    print("[bench] start", file=sys.stderr, flush=True)
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
         dst = torch.empty_like(src)
@@ -301,12 +387,20 @@ def main():
         c_tok = np.zeros(nch)
         np.add.at(c_tok, tiles["chunk"], tiles["tok_end"] - tiles["tok_begin"])
         rate = head / np.maximum(c_tok[:len(head)], 1)               # microseconds per token of the chunk
+        # per tile: run time per token over the full-size tiles (at least half the largest tile's tokens); cuts snap
+        # to boundaries, so tile sizes differ by design and only the per-token time is comparable between them
+        t_tok = (tiles["tok_end"] - tiles["tok_begin"]).astype(np.float64)
+        t_us = (c[:, 1] - c[:, 0]) / 100.0
+        big = t_tok >= 0.5 * t_tok.max()
+        t_rate = t_us[big] / t_tok[big]
         extra = {"chunks": int(nch), "tiles": int(db.plan.num_tiles), "workgroups": n_wg,
                  "wg_finish_us_mean": float(finish.mean()), "wg_finish_us_max": float(finish.max()),
                  "straggle_wg_finish_max_over_mean": float(finish.max() / finish.mean()),
                  "equal_chunk_us_mean": float(head.mean()), "equal_chunk_us_max": float(head.max()),
                  "straggle_equal_chunk_max_over_mean": float(head.max() / head.mean()),
-                 "straggle_equal_chunk_per_token_max_over_mean": float(rate.max() / rate.mean())}
+                 "straggle_equal_chunk_per_token_max_over_mean": float(rate.max() / rate.mean()),
+                 "full_size_tiles": int(big.sum()),
+                 "straggle_full_size_tile_per_token_max_over_mean": float(t_rate.max() / t_rate.mean())}
 
     default_plan = (args.tile_tokens == 0 and not args.merge_all and not args.graph and args.num_long == 3 and
                     not any(k.startswith("NANOCP_") for k in os.environ))
@@ -343,6 +437,15 @@ def main():
                                       "kernel plus the tile-reduction kernel")
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(batch)
+    if not args.no_per_config and args.config == 3 and default_plan:
+        # the other workloads at the same --steps / --warmup, each in its default launch configuration
+        del db, pools, parts_o, parts_lse, out, local_o, local_lse
+        torch.cuda.empty_cache()
+        result["per_config"] = {}
+        for cid in (2, 4, 5, 6, 7):
+            result["per_config"][str(cid)] = quick_config(cid, args.steps, args.warmup)
+            print(f"[bench] config {cid}: {result['per_config'][str(cid)]['us_per_step']:.1f} us/step", file=sys.stderr,
+                  flush=True)
     print(json.dumps(result))
 
 

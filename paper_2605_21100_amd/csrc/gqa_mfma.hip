@@ -25,6 +25,7 @@
 #include <cstdlib>
 #include <type_traits>
 
+#include "arrive.h"
 #include "epilogue.h"
 #include "plan.h"
 
@@ -64,15 +65,6 @@ template <bool kNT>
 __device__ inline u32x4 ldg16(const void* base, uint32_t byte_off) {
   const u32x4* ptr = (const u32x4*)((const char*)base + byte_off);
   return kNT ? __builtin_nontemporal_load(ptr) : *ptr;
-}
-
-// Partials that another workgroup will read inside the same launch travel with device-scope
-// (L2-coherent across XCDs) stores and loads, so no cache-wide write-back or invalidate is needed.
-__device__ inline void st_dev(float* ptr, float v) {
-  __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline float ld_dev(const float* ptr) {
-  return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __device__ inline uint32_t pack_bf16(float a, float b) {
@@ -471,16 +463,8 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) st_dev(dst_o + 16 * e, o[e]);
         if (c16 == 0) st_dev(p.ws_lse + (size_t)tile.dst * kG + n, lse_nat);
-        // Every thread's device-scope stores must have been acknowledged before the arrival is counted: the
-        // workgroup-scope fence orders them for the compiler but waits for nothing on this target (one CU, one
-        // L1), and a store still in flight could be overtaken by the counter's atomic, which goes to another
-        // channel - the reducing workgroup would then read a stale partial.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __syncthreads();
-        if (tid == 0) arrive_s = atomicAdd(&p.sync[kSyncSegBase + tile.seg], 1);
-        __syncthreads();
-        if (arrive_s == tile.n_parts - 1) {
+        // publish, count the arrival, and reduce if this workgroup delivered the last partial (csrc/arrive.h)
+        if (arrive_is_last(&p.sync[kSyncSegBase + tile.seg], tile.n_parts, &arrive_s)) {
           const float* wl = p.ws_lse + (size_t)tile.slot_begin * kG + n;
           const float* wo = p.ws_o + ((size_t)tile.slot_begin * kG + n) * kD + c16;
           float top = -INFINITY;
@@ -511,7 +495,7 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) fo[16 * e] = r8[e] * rinv;
           }
-          if (tid == 0) p.sync[kSyncSegBase + tile.seg] = 0;  // ready for the next launch
+          if (tid == 0) arrive_reset(&p.sync[kSyncSegBase + tile.seg]);  // ready for the next launch
         }
       }
     }
