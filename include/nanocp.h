@@ -80,8 +80,9 @@ typedef struct {
   int32_t page_size;     /* ps, tokens per page */
   float softmax_scale;   /* score = softmax_scale * <q, k> */
   float out_scale;       /* FP8 output rows only (out_dtype / final_dtype = NANOCP_FP8_E4M3): the stored code is
-                            e4m3(value / out_scale), round to nearest even, saturating at +-448 -- a static scale the
-                            caller supplies, as consumers of fp8 activations do.  0 means 1.  Ignored otherwise. */
+                            e4m3(value * (1 / out_scale)), the reciprocal rounded to float once, the product rounded to
+                            nearest even and saturating at +-448 -- a static scale the caller supplies, as consumers
+                            of fp8 activations do.  0 means 1.  Ignored otherwise. */
 } nanocp_attn_desc;
 
 /* One shard entry = one row of the attention batch of this instance: a whole local request, or
@@ -171,7 +172,7 @@ nanocp_status nanocp_decode_attn_partial(const nanocp_plan* plan, const void* q,
  *   lse_parts  DEVICE [num_parts, Hq]     float    partials received from other instances)
  *   part_offsets DEVICE [num_out + 1] int32; part_index DEVICE [part_offsets[num_out]] int32, or NULL for identity
  *   out        DEVICE [num_out, Hq, Dv] of out_dtype: NANOCP_F32, NANOCP_BF16, or NANOCP_FP8_E4M3 (one byte per
- *              element, the code of value / desc->out_scale; see nanocp_attn_desc)
+ *              element, the code of value scaled by 1 / desc->out_scale; see nanocp_attn_desc)
  *   out_lse    DEVICE [num_out, Hq] float, or NULL
  * Partials with lse = -inf are ignored; if all are, O = 0 and LSE = -inf.  Only Hq, Dv and out_scale of desc are
  * used.

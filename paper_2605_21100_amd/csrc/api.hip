@@ -26,7 +26,7 @@ __global__ __launch_bounds__(kThreads) void reduce_tiles_kernel(const Seg* __res
                                                                 float* __restrict__ out_o, float* __restrict__ out_lse,
                                                                 void* __restrict__ final_out,
                                                                 float* __restrict__ final_lse, int final_kind,
-                                                                float out_scale,
+                                                                float out_inv_scale,
                                                                 const int32_t* __restrict__ header, int Hq, int G,
                                                                 int Dv) {
   if (header && (int)blockIdx.x >= header[1]) return;  // plan image: launched for the bucket's capacity
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(kThreads) void reduce_tiles_kernel(const Seg* __res
     // the shard is the only partial of its output row: final form, no merge needed
     const size_t fi = ((size_t)sg.final_row * Hq + (size_t)sg.kv_head * G) * Dv + (size_t)i4 * 4;
     const float o4[4] = {acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
-    store_final<4>(final_out, fi, final_kind, out_scale, o4);
+    store_final<4>(final_out, fi, final_kind, out_inv_scale, o4);
     if (final_lse && (i4 % q4) == 0) final_lse[(size_t)sg.final_row * Hq + (size_t)sg.kv_head * G + g] = lse;
     return;
   }
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float* __restrict
                                                          const int32_t* __restrict__ part_index,
                                                          const int32_t* __restrict__ out_rows,
                                                          const int32_t* __restrict__ num_out_dev, void* __restrict__ out,
-                                                         float* __restrict__ out_lse, int out_kind, float out_scale,
+                                                         float* __restrict__ out_lse, int out_kind, float out_inv_scale,
                                                          int Hq, int Dv) {
   if (num_out_dev && (int)blockIdx.x >= *num_out_dev) return;  // launched for a capacity, the count is on the device
   const int b = part_offsets[blockIdx.x], e = part_offsets[blockIdx.x + 1];
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float* __restrict
     lse = top + logf(tot);
   }
   const size_t oi = (size_t)r * row + (size_t)i4 * 4;
-  store_final<4>(out, oi, out_kind, out_scale, acc);
+  store_final<4>(out, oi, out_kind, out_inv_scale, acc);
   if (out_lse && (i4 % q4) == 0) out_lse[(size_t)r * Hq + a] = lse;
 }
 
@@ -191,7 +191,7 @@ nanocp_status launch_tiles_and_reduce(const nanocp_attn_desc& d, int variant, co
     if (p.Dv % 4) return NANOCP_ESHAPE;
     const unsigned per_seg = (unsigned)((p.G * (p.Dv / 4) + kThreads - 1) / kThreads);
     hipLaunchKernelGGL(reduce_tiles_kernel, dim3((unsigned)num_segs, per_seg), dim3(kThreads), 0, st, d_segs, p.ws_o,
-                       p.ws_lse, p.out_o, p.out_lse, p.final_out, p.final_lse, p.final_kind, p.out_scale, p.header, p.Hq, p.G, p.Dv);
+                       p.ws_lse, p.out_o, p.out_lse, p.final_out, p.final_lse, p.final_kind, p.out_inv_scale, p.header, p.Hq, p.G, p.Dv);
     if (hipGetLastError() != hipSuccess) return NANOCP_EHIP;
   }
   return NANOCP_OK;
@@ -247,7 +247,7 @@ nanocp_status run_partial(const nanocp_plan* plan, const void* q, const void* k_
   p.final_out = final_out;
   p.final_lse = final_out ? final_lse : nullptr;
   p.final_kind = final_out ? final_dtype : NANOCP_F32;
-  p.out_scale = out_scale_of(d);
+  p.out_inv_scale = out_inv_scale_of(d);
   p.variant = plan->variant;
   p.Hq = d.num_q_heads;
   p.Hkv = d.num_kv_heads;
@@ -313,7 +313,7 @@ nanocp_status run_image(const nanocp_attn_desc* desc, const nanocp_bucket* bucke
   p.final_out = final_out;
   p.final_lse = final_out ? final_lse : nullptr;
   p.final_kind = final_out ? final_dtype : NANOCP_F32;
-  p.out_scale = out_scale_of(d);
+  p.out_inv_scale = out_inv_scale_of(d);
   p.variant = variant;
   p.Hq = d.num_q_heads;
   p.Hkv = d.num_kv_heads;
@@ -462,7 +462,7 @@ nanocp_status nanocp_merge_partials_dyn(const nanocp_attn_desc* desc, const floa
   dim3 grid((unsigned)num_out, (unsigned)per_out);
   hipStream_t st = (hipStream_t)stream;
   hipLaunchKernelGGL(nanocp::merge_kernel, grid, dim3(nanocp::kThreads), 0, st, o_parts, lse_parts, part_offsets,
-                     part_index, out_rows, num_out_dev, out, out_lse, out_dtype, nanocp::out_scale_of(*desc), Hq, Dv);
+                     part_index, out_rows, num_out_dev, out, out_lse, out_dtype, nanocp::out_inv_scale_of(*desc), Hq, Dv);
   return hipGetLastError() == hipSuccess ? NANOCP_OK : NANOCP_EHIP;
 }
 

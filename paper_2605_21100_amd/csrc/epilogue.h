@@ -17,26 +17,19 @@ __device__ inline uint32_t f32_to_bf16_rne(float f) {
   return u >> 16;
 }
 
-// float -> OCP FP8 E4M3FN code (bias 7, max 448, no infinity): round to nearest even, saturating; NaN -> 0x7f.
-// Written with integer arithmetic from the format's definition, so the result does not depend on a conversion
-// instruction's saturation mode.
-__device__ inline uint32_t f32_to_e4m3(float f) {
-  const uint32_t u = __float_as_uint(f);
-  const uint32_t sign = (u >> 24) & 0x80u;
-  uint32_t a = u & 0x7fffffffu;
-  if (a > 0x7f800000u) return sign | 0x7fu;
-  if (a >= 0x43e00000u) return sign | 0x7eu;  // |f| >= 448 (infinity included): the largest finite code
-  if (a < 0x3c800000u) {                      // below 2^-6: multiples of 2^-9; 8 * 2^-9 is the smallest normal, code 8
-    return sign | (uint32_t)__float2int_rn(__uint_as_float(a) * 512.f);
-  }
-  a += 0x7ffffu + ((a >> 20) & 1u);           // keep 3 fraction bits, ties to even (a carry moves to the exponent)
-  return sign | ((a >> 20) - (120u << 3));    // rebias 127 -> 7; at most 0x7e because a < 448 rounds to <= 448
+// Two floats -> two OCP FP8 E4M3FN codes in the low 16 bits (first value in the low byte): round to nearest even,
+// saturating at +-448 (the format has no infinity; the conversion instruction alone would produce NaN beyond the
+// range), NaN -> a NaN code.  gfx950's packed conversion produces the OCP format; the saturation is done here.
+__device__ inline uint32_t f32x2_to_e4m3(float a, float b) {
+  a = a != a ? a : __builtin_amdgcn_fmed3f(a, -448.f, 448.f);  // the clamp must not turn a NaN into a number
+  b = b != b ? b : __builtin_amdgcn_fmed3f(b, -448.f, 448.f);
+  return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false) & 0xffffu;
 }
 
 // Store N consecutive elements (N = 1, 4 or 8; idx a multiple of N) of a final row.
-// kind: NANOCP_F32, NANOCP_BF16, or NANOCP_FP8_E4M3 (code of value / scale).
+// kind: NANOCP_F32, NANOCP_BF16, or NANOCP_FP8_E4M3 (code of value * inv_scale, inv_scale = 1 / out_scale in fp32).
 template <int N>
-__device__ inline void store_final(void* out, size_t idx, int kind, float scale, const float (&v)[N]) {
+__device__ inline void store_final(void* out, size_t idx, int kind, float inv_scale, const float (&v)[N]) {
   static_assert(N == 1 || N == 4 || N == 8, "vector width");
   if (kind == NANOCP_F32) {
     float* o = (float*)out + idx;
@@ -60,13 +53,13 @@ __device__ inline void store_final(void* out, size_t idx, int kind, float scale,
   } else {
     uint8_t* o = (uint8_t*)out + idx;
     if (N == 1) {
-      o[0] = (uint8_t)f32_to_e4m3(v[0] / scale);
+      o[0] = (uint8_t)f32x2_to_e4m3(v[0] * inv_scale, 0.f);
     } else {
       uint32_t w[N >= 4 ? N / 4 : 1];
 #pragma unroll
       for (int i = 0; i < N / 4; ++i)
-        w[i] = f32_to_e4m3(v[4 * i] / scale) | (f32_to_e4m3(v[4 * i + 1] / scale) << 8) |
-               (f32_to_e4m3(v[4 * i + 2] / scale) << 16) | (f32_to_e4m3(v[4 * i + 3] / scale) << 24);
+        w[i] = f32x2_to_e4m3(v[4 * i] * inv_scale, v[4 * i + 1] * inv_scale) |
+               (f32x2_to_e4m3(v[4 * i + 2] * inv_scale, v[4 * i + 3] * inv_scale) << 16);
       if (N == 4) *(uint32_t*)o = w[0];
       if (N == 8) *(uint2*)o = make_uint2(w[0], w[N == 8 ? 1 : 0]);
     }
@@ -81,6 +74,7 @@ __device__ inline void store_final_zero(void* out, size_t idx, int kind) {
 }
 
 inline bool final_dtype_ok(int dt) { return dt == NANOCP_F32 || dt == NANOCP_BF16 || dt == NANOCP_FP8_E4M3; }
-inline float out_scale_of(const nanocp_attn_desc& d) { return d.out_scale > 0.f ? d.out_scale : 1.f; }
+// multiplier of the fp8 epilogue: 1 / out_scale rounded to fp32 (out_scale <= 0 means 1)
+inline float out_inv_scale_of(const nanocp_attn_desc& d) { return d.out_scale > 0.f ? 1.f / d.out_scale : 1.f; }
 
 }  // namespace nanocp

@@ -176,7 +176,7 @@ __global__ __launch_bounds__(kThreads) void generic_partial_kernel(KParams p) {
           if (o < GH * Dv) {
             const float v = acc[i] / l_s[o / Dv];
             const float v1[1] = {v};
-            store_final<1>(p.final_out, fo + o, p.final_kind, p.out_scale, v1);
+            store_final<1>(p.final_out, fo + o, p.final_kind, p.out_inv_scale, v1);
           }
         }
         if (tid < GH) {

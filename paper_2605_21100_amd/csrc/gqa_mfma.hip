@@ -130,7 +130,10 @@ struct StepRegs {
   float ks, vs;  // fp8 scales of the step's page
 };
 
-template <bool kFp8, bool kNT>
+// kOut: element type of the final rows (nanocp_dtype), a compile-time constant so that each instantiation carries
+// one output epilogue only -- the kernel's run time is sensitive to its instruction footprint (every tile walks
+// through prologue and epilogue code that is cold by then).
+template <bool kFp8, bool kNT, int kOut>
 __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
   constexpr int kStep = kFp8 ? 64 : 32;            // tokens per step
   constexpr int kEl = kFp8 ? 1 : 2;                // bytes per kv element
@@ -443,7 +446,7 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
         if (p.final_out && tile.final_row >= 0) {
           // the shard alone is an output row: written in its final form, no merge needed
           const size_t fo = ((size_t)tile.final_row * p.Hq + (size_t)h * kG + n) * kD + d0;
-          store_final<8>(p.final_out, fo, p.final_kind, p.out_scale, o);
+          store_final<8>(p.final_out, fo, kOut, p.out_inv_scale, o);
           if (c16 == 0 && p.final_lse) p.final_lse[(size_t)tile.final_row * p.Hq + (size_t)h * kG + n] = lse_nat;
         } else {
           float* dst_o = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG + n) * kD + d0;
@@ -487,7 +490,7 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
               const float v1[1] = {r8[e] * rinv};
-              store_final<1>(p.final_out, fi + 16 * e, p.final_kind, p.out_scale, v1);
+              store_final<1>(p.final_out, fi + 16 * e, kOut, p.out_inv_scale, v1);
             }
             if (c16 == 0 && p.final_lse) p.final_lse[(size_t)tile.final_row * p.Hq + (size_t)h * kG + n] = lse_f;
           } else {
@@ -522,7 +525,7 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
       if ((tid & 15) == 0) p.out_lse[(size_t)sg.shard * p.Hq + head] = -INFINITY;
       if (p.final_out && sg.final_row >= 0) {
         const size_t fo = ((size_t)sg.final_row * p.Hq + head) * kD + d0;
-        store_final_zero<8>(p.final_out, fo, p.final_kind);
+        store_final_zero<8>(p.final_out, fo, kOut);
         if ((tid & 15) == 0 && p.final_lse) p.final_lse[(size_t)sg.final_row * p.Hq + head] = -INFINITY;
       } else {
         float* dst_o = p.out_o + ((size_t)sg.shard * p.Hq + head) * kD + d0;
@@ -543,6 +546,16 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
 
 }  // namespace
 
+template <bool kFp8, bool kNT>
+void launch_out(const KParams& p, dim3 grid, dim3 block, hipStream_t st) {
+  if (p.final_kind == NANOCP_BF16)
+    hipLaunchKernelGGL((gqa_mfma_kernel<kFp8, kNT, NANOCP_BF16>), grid, block, 0, st, p);
+  else if (p.final_kind == NANOCP_FP8_E4M3)
+    hipLaunchKernelGGL((gqa_mfma_kernel<kFp8, kNT, NANOCP_FP8_E4M3>), grid, block, 0, st, p);
+  else
+    hipLaunchKernelGGL((gqa_mfma_kernel<kFp8, kNT, NANOCP_F32>), grid, block, 0, st, p);
+}
+
 hipError_t launch_gqa_mfma(int variant, const KParams& p, int num_blocks, hipStream_t st) {
   dim3 grid(num_blocks), block(kThreads);
   // K/V are read exactly once: the streaming (non-temporal) loads are the product path.  A -DNANOCP_TUNING build can
@@ -552,22 +565,19 @@ hipError_t launch_gqa_mfma(int variant, const KParams& p, int num_blocks, hipStr
     const char* v = std::getenv("NANOCP_KV_NONTEMPORAL");
     return !(v && v[0] == '0');
   }();
-#else
-  constexpr bool nt = true;
-#endif
-  if (variant == kGqaMfmaBf16) {
-    if (nt)
-      hipLaunchKernelGGL((gqa_mfma_kernel<false, true>), grid, block, 0, st, p);
-    else
-      hipLaunchKernelGGL((gqa_mfma_kernel<false, false>), grid, block, 0, st, p);
-  } else if (variant == kGqaMfmaFp8) {
-    if (nt)
-      hipLaunchKernelGGL((gqa_mfma_kernel<true, true>), grid, block, 0, st, p);
-    else
-      hipLaunchKernelGGL((gqa_mfma_kernel<true, false>), grid, block, 0, st, p);
-  } else {
-    return hipErrorInvalidValue;
+  if (!nt) {
+    if (variant == kGqaMfmaBf16) launch_out<false, false>(p, grid, block, st);
+    else if (variant == kGqaMfmaFp8) launch_out<true, false>(p, grid, block, st);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
   }
+#endif
+  if (variant == kGqaMfmaBf16)
+    launch_out<false, true>(p, grid, block, st);
+  else if (variant == kGqaMfmaFp8)
+    launch_out<true, true>(p, grid, block, st);
+  else
+    return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

@@ -379,7 +379,7 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
           for (int dvb = 0; dvb < kDv / 16; ++dvb) {
             const f32x4 v = acc[hb][dvb] * inv;
             const float v4[4] = {v[0], v[1], v[2], v[3]};
-            store_final<4>(p.final_out, fo + 16 * dvb, p.final_kind, p.out_scale, v4);
+            store_final<4>(p.final_out, fo + 16 * dvb, p.final_kind, p.out_inv_scale, v4);
             if ((dvb & 3) == 3) __builtin_amdgcn_sched_barrier(0);
           }
           if (g == 0 && p.final_lse) p.final_lse[(size_t)tile.final_row * kHq + head] = lse;

@@ -62,7 +62,7 @@ struct KParams {
   void* final_out;       // [num_out, Hq, Dv] float, bf16 or fp8; null = every shard writes out_o / out_lse
   float* final_lse;      // [num_out, Hq], may be null
   int32_t final_kind;    // nanocp_dtype of final_out
-  float out_scale;       // fp8 final rows: code of value / out_scale
+  float out_inv_scale;   // fp8 final rows: code of value * out_inv_scale
   int32_t variant;       // the tile kernel this launch runs (checked against a plan image's header)
   int32_t Hq, Hkv, G, Dk, Dv, ps, max_blocks, kind;
   float scale;

@@ -1,5 +1,5 @@
 """FP8 (OCP E4M3FN) output epilogue of the Phase 4 merge and of the final rows written by the attention kernels:
-stored code = e4m3(value / out_scale), round to nearest even, saturating, with a caller-supplied static scale.
+stored code = e4m3(value * (1 / out_scale)), round to nearest even, saturating, with a caller-supplied static scale.
 
 Checked (i) against the format itself: the device encoder must agree bit for bit with the generators' numpy encoder
 on a dense set of values (every code, every rounding boundary and its float32 neighbours, the subnormal range, the
@@ -59,7 +59,7 @@ def test_device_e4m3_encoder_matches_the_format():
     x = np.concatenate([np.asarray(v, np.float32) for v in vals])
     for scale in (1.0, 0.0371, 4.0):
         got = _merge_identity(x, scale)
-        want = numfmt.f32_to_e4m3fn(x / np.float32(scale))
+        want = numfmt.f32_to_e4m3fn(x * (np.float32(1) / np.float32(scale)))
         bad = np.nonzero(got != want)[0]
         assert bad.size == 0, (scale, x[bad[:5]], got[bad[:5]], want[bad[:5]])
     # every code decodes (the checker's table, written from the format) and re-encodes to itself
@@ -101,7 +101,8 @@ def test_fp8_final_rows_and_merge(cid, tile_tokens):
         torch.cuda.synchronize()
         res[dt] = out.cpu().numpy()
     f32, q8 = res[torch.float32], res[torch.uint8]
-    assert np.array_equal(q8, numfmt.f32_to_e4m3fn(f32 / np.float32(out_scale))), "fp8 rows != encoder(f32 rows)"
+    inv = np.float32(1) / np.float32(out_scale)
+    assert np.array_equal(q8, numfmt.f32_to_e4m3fn(f32 * inv)), "fp8 rows != encoder(f32 rows)"
     want = numfmt.f32_to_e4m3fn((ref_m / out_scale).astype(np.float32))
     step = np.abs(_ordered(q8) - _ordered(want))
     assert step.max() <= 1, int(step.max())
@@ -135,5 +136,5 @@ def test_fp8_output_full_size(cid):
                                          out_rows=torch.from_numpy(db.rest_rows).cuda())
         torch.cuda.synchronize()
         res[dt] = out.cpu().numpy()
-    assert np.array_equal(res[torch.uint8], numfmt.f32_to_e4m3fn(res[torch.float32] / np.float32(out_scale)))
+    assert np.array_equal(res[torch.uint8], numfmt.f32_to_e4m3fn(res[torch.float32] * (np.float32(1) / np.float32(out_scale))))
     db.plan.close()
