@@ -14,6 +14,7 @@ namespace nanocp {
 hipError_t launch_generic(const nanocp_attn_desc& d, const KParams& p, int num_blocks, hipStream_t st);
 hipError_t launch_gqa_mfma(int variant, const KParams& p, int num_blocks, hipStream_t st);
 hipError_t launch_mla_mfma(const KParams& p, int num_blocks, hipStream_t st);
+hipError_t launch_mla_reduce(const KParams& p, const Seg* segs, int num_segs, hipStream_t st);
 
 namespace {
 
@@ -185,9 +186,13 @@ nanocp_status launch_tiles_and_reduce(const nanocp_attn_desc& d, int variant, co
       e = launch_gqa_mfma(variant, p, blocks, st);
     if (e != hipSuccess) return NANOCP_EHIP;
   }
-  // the fused variants' only segments are (shard, head) pairs without tokens, which their tile kernel fills itself
+  // the GQA MFMA variants reduce inside the tile kernel; their only segments are (shard, head) pairs without tokens,
+  // which the tile kernel fills itself.  The MLA variant has a reduction kernel of its own (its partials are stored
+  // in register order); the generic variant's segments go through reduce_tiles_kernel.
   const bool fills_own = blocks > 0 && (variant == kGqaMfmaBf16 || variant == kGqaMfmaFp8);
-  if (num_segs > 0 && !fills_own) {
+  if (num_segs > 0 && variant == kMlaMfmaBf16) {
+    if (launch_mla_reduce(p, d_segs, num_segs, st) != hipSuccess) return NANOCP_EHIP;
+  } else if (num_segs > 0 && !fills_own) {
     if (p.Dv % 4) return NANOCP_ESHAPE;
     const unsigned per_seg = (unsigned)((p.G * (p.Dv / 4) + kThreads - 1) / kThreads);
     hipLaunchKernelGGL(reduce_tiles_kernel, dim3((unsigned)num_segs, per_seg), dim3(kThreads), 0, st, d_segs, p.ws_o,

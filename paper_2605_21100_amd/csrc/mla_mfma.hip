@@ -4,16 +4,30 @@
 // Paper: Data Plane, Phase 2 (partial attention + LSE over the local KV partition); the MoE-bound
 // instance's Q row has hidden size 512 (+64) and 128 heads.
 //
-// One workgroup = 8 wavefronts (two per SIMD) = one chunk of the work queue at a time, one workgroup per CU.
-// A page (72 KB) is copied HBM -> LDS by direct-to-LDS 16-byte loads (no registers in between) into one of
-// two buffers while the previous page is being computed.  Wavefront w owns query heads 16w..16w+15; its Q
-// fragments (72 registers) and its 16 x 512 accumulator (128 registers) stay resident for the whole tile:
-//   scores:  S^T[token, head] = K[token, :] . Q[head, :]     A = K rows from LDS (ds_read_b128), B = Q (registers)
-//   output:  O^T[dim, head]  += V^T[dim, token] P^T[token, head]   A = V^T via the LDS transpose read
-//            (ds_read_b64_tr_b16: 16 lanes fetch a 4-token x 16-dim block, each lane gets 4 tokens of one dim)
-// so no wavefront needs another's probabilities or accumulators; the only barriers are the two per page
-// that guard the LDS buffers.  P is split into two bf16 terms as in the GQA kernels.
+// One workgroup = W wavefronts (8 for 128 heads: two per SIMD) = one chunk of the work queue at a time, one
+// workgroup per CU.  A page (72 KB) is copied HBM -> LDS by direct-to-LDS 16-byte loads (no registers in between)
+// while the previous page is being computed.  The two products are split over the wavefronts in different ways:
+//   scores (split by heads):  wavefront w owns query heads 16w..16w+15, its Q fragments stay in registers
+//       S^T[token, head] = K[token, :] . Q[head, :]          A = K rows from LDS (ds_read_b128), B = Q
+//     followed by the online softmax of those heads; the probabilities go to LDS as fp16 B-operand fragments.
+//   output (split by V dims): wavefront w owns dims 512/W * w .. of ALL heads (accumulator 512/W x 16W, 128 registers)
+//       O^T[dim, head] += V^T[dim, token] P^T[token, head]   A = V^T via the LDS transpose read
+//       (ds_read_b64_tr_b16: 16 lanes fetch a 4-token x 16-dim block, each lane gets 4 tokens of one dim), B = P
+//     so every V^T fragment is fetched from LDS once per page (not once per wavefront) and feeds 16W / 16 matrix
+//     instructions; the only data all wavefronts read are the probabilities (16 KB per page, 16-byte reads).
+// Precision of P.  One fp16 term (11 significant bits) instead of the two bf16 terms of the GQA kernels: the P.V
+// product is then half the matrix instructions.  Two things make that sufficient:
+//   * the softmax reference is an INTEGER exponent m (a ceiling of log2-domain scores, see kHeadroom), and
+//     p = 2^frac(y) * 2^(floor(y) - m): the significand of p does not depend on m, every rescale is an exact
+//     power of two, so a token's rounded probability is the same number (up to that power of two) whatever tile
+//     or shard it is processed in -- a request's merged partials and its unsharded result differ only by fp32
+//     summation order;
+//   * V (bf16, 8 significant bits) is widened to fp16 exactly (in registers, by the wavefront that owns the dims).
+//     fp16's range applies: |V| above 65504 saturates, |V| below 6e-8 flushes to zero.  P is scaled by a power of
+//     two so that probabilities down to 2^-28 of the largest possible maximum stay normal fp16 numbers.
 // LDS rows are XOR-swizzled in units of 16 bytes so that both read patterns are bank-conflict free.
+// The tiles of one (shard, head-set) that was cut are combined by mla_reduce_kernel below, launched right after the
+// tile kernel (it also writes the rows of shards without tokens).
 #include <hip/hip_runtime.h>
 
 #include <mutex>
@@ -26,27 +40,40 @@ namespace nanocp {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kDk = 576, kDv = 512, kPS = 64;
-constexpr int kHB = 1;  // 16-head blocks per wavefront (2 was measured: half the LDS reads, but Q and O no longer fit 256 registers)
-// kKD, kVD below: how far the LDS reads run ahead of the matrix instructions that use them (K: units of two
-// fragments, V: fragments); bounded by the registers left beside Q and the accumulators: (1, 2) with 256 registers
-// per wavefront.  Measured with 512 registers (64-head variant): going deeper than this does not help -- the
-// transpose read itself is the limit (about 100 B/clk per CU against 210 for 16-byte reads, measured with a
-// stand-alone probe), and it carries 64 KB per wavefront and page.
-constexpr int kMla64KD = 2, kMla64VD = 4;
 constexpr int kRowBytes = kDk * 2;        // 1152: one token's latent row in HBM
 constexpr int kRowA = kDv * 2;            // 1024: dims 0..511 (the V part), LDS region A row
 constexpr int kRowB = (kDk - kDv) * 2;    // 128:  dims 512..575 (rope part), LDS region B row
-constexpr int kRegionA = kPS * kRowA;     // 65536
-constexpr int kBufBytes = kRegionA + kPS * kRowB;  // 73728 per page buffer
+constexpr int kRegionA = kPS * kRowA;     // 65536 per page buffer
 constexpr int kSteps = kDk / 32;          // 18 k-steps of 32 dims
 constexpr int kStepsA = kDv / 32;         // 16 of them in region A
+// Probabilities are handed to the matrix cores as 2^(y - m_ref) * 2^kPShift, where m_ref is a per-head integer
+// REFERENCE exponent that is allowed to lag the running maximum by up to kHeadroom: it moves (and the accumulators
+// are rescaled, by an exact power of two) only when a score exceeds it by more than that -- after a tile's first page
+// almost never, whereas the running maximum of 128 heads moves on nearly every page.  Largest value fed to the
+// matrix cores: 2^(kHeadroom + kPShift) = 2^14 (fp16 holds up to 2^16); values stay normal fp16 numbers down to
+// 2^-20 of the reference (2^-28 of the largest possible maximum).
+constexpr int kHeadroom = 8;
+constexpr int kPShift = 6;
+constexpr float kMaskedScore = -1073741824.f;  // -2^30: score of a token slot outside the tile's range
+
+// LDS map: two buffers for the V part of a page (double-buffered: the copy of page n+1 runs under the compute of
+// page n), ONE for the rope part (only the score product reads it; it is refilled as soon as that product is done),
+// the probabilities of one page, and the small per-head exchange arrays.
+constexpr int kOffRope = 2 * kRegionA;                  // 131072, 8 KB
+constexpr int kOffP = kOffRope + kPS * kRowB;           // 139264, up to 16 KB: [head block][token half][lane] x 16 B
+constexpr int kOffAlpha = kOffP + 8 * 2 * 1024;         // [16 r][8 hb] floats: this page's accumulator rescale factors
+constexpr int kOffM = kOffAlpha + 512;                  // [128] per-head running maximum (tile end)
+constexpr int kOffL = kOffM + 512;                      // [128] per-head sum of probabilities (tile end)
+constexpr int kLdsBytes = kOffL + 512;                  // 157184
 
 template <typename T>
 using cptr = const __attribute__((address_space(4))) T*;
@@ -55,6 +82,7 @@ __device__ inline cptr<T> as_const(const T* ptr) {
   return (cptr<T>)(uintptr_t)ptr;
 }
 typedef __attribute__((address_space(3))) char* lds_ptr;
+#define LDS_AS(T, ptr) ((__attribute__((address_space(3))) T*)(ptr))
 
 // 64 lanes x 16 bytes from global (scalar base + per-lane offset) straight into LDS at lds_addr + 16*lane
 __device__ inline void dma16(uint64_t base, uint32_t lane_off, uint32_t lds_addr) {
@@ -64,53 +92,48 @@ __device__ inline void dma16(uint64_t base, uint32_t lane_off, uint32_t lds_addr
 // workgroup barrier without the memory fences of __syncthreads(): copies in flight stay in flight
 __device__ inline void wg_barrier() { __builtin_amdgcn_s_barrier(); }
 
-__device__ inline f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+__device__ inline f32x4 mfma_bf16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
-__device__ inline uint32_t pack_bf16(float a, float b) {
-  bf16x2 v = {(__bf16)a, (__bf16)b};
-  return __builtin_bit_cast(uint32_t, v);
+__device__ inline f32x4 mfma_f16(f16x8 a, f16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
-__device__ inline void split8(const float* p, bf16x8& hi, bf16x8& lo) {
-  u32x4 h, l;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t hp = pack_bf16(p[2 * i], p[2 * i + 1]);
-    const float h0 = __uint_as_float(hp << 16), h1 = __uint_as_float(hp & 0xffff0000u);
-    h[i] = hp;
-    l[i] = pack_bf16(p[2 * i] - h0, p[2 * i + 1] - h1);
-  }
-  hi = __builtin_bit_cast(bf16x8, h);
-  lo = __builtin_bit_cast(bf16x8, l);
+// two bf16 (one dword) -> two fp16 (one dword), exact inside fp16's range (the conversion rounds toward zero, which
+// only matters outside it: too large saturates to 65504, too small flushes toward zero)
+__device__ inline uint32_t bf16x2_to_f16x2(uint32_t w) {
+  const float lo = __uint_as_float(w << 16), hi = __uint_as_float(w & 0xffff0000u);
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+}
+__device__ inline uint32_t pack_f16(float a, float b) {
+  f16x2 v = {(_Float16)a, (_Float16)b};  // round to nearest even
+  return __builtin_bit_cast(uint32_t, v);
 }
 // Butterfly over the four 16-lane rows of a wavefront (lanes l, l^16, l^32, l^48 hold the same head) with the
 // row-swap instructions of the vector ALU (v_permlane16_swap / v_permlane32_swap) -- no trip through LDS.
-// swap16(x, x) = {rows x0 x0 x2 x2, rows x1 x1 x3 x3};  swap32(x, x) = {x0 x1 x0 x1, x2 x3 x2 x3}.
 __device__ inline float xor_max(float v) {
-  typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
   const uint32_t u = __float_as_uint(v);
-  const u32x2_t a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const u32x2 a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
   const float w = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
   const uint32_t uw = __float_as_uint(w);
-  const u32x2_t b = __builtin_amdgcn_permlane32_swap(uw, uw, false, false);
+  const u32x2 b = __builtin_amdgcn_permlane32_swap(uw, uw, false, false);
   return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 __device__ inline float xor_sum(float v) {
-  typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
   const uint32_t u = __float_as_uint(v);
-  const u32x2_t a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const u32x2 a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
   const float w = __uint_as_float(a[0]) + __uint_as_float(a[1]);
   const uint32_t uw = __float_as_uint(w);
-  const u32x2_t b = __builtin_amdgcn_permlane32_swap(uw, uw, false, false);
+  const u32x2 b = __builtin_amdgcn_permlane32_swap(uw, uw, false, false);
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
-
-// kMlaWaves wavefronts of 16 heads each: 8 for 128 query heads (DeepSeek-V3-like), 4 for 64 (Kimi-K2-like)
-template <int kMlaWaves, int kKD, int kVD>
+// W wavefronts: 8 for 128 query heads (DeepSeek-V3-like), 4 for 64 (Kimi-K2-like).
+// kKD: how many score-product units (two K fragments each) the LDS reads run ahead of the matrix instructions.
+template <int W, int kKD, int kOut>
 __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
-  constexpr int kHq = 16 * kHB * kMlaWaves;
-  constexpr int kSlabs = 8 / kMlaWaves;  // rope slabs (8 rows each) one wavefront copies
-  extern __shared__ __attribute__((aligned(16))) char smem[];  // 2 page buffers
+  constexpr int kHq = 16 * W;        // query heads = head blocks of 16 x W
+  constexpr int kDW = 32 / W;        // 16-dim blocks of V one wavefront owns (4 or 8)
+  constexpr int kSlabs = 8 / W;      // rope slabs (8 rows each) one wavefront copies
+  extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int next_s;
 
   const int tid = threadIdx.x;
@@ -122,40 +145,33 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
 
   const cptr<int32_t> chunk_offsets = as_const(p.chunk_offsets);
   const cptr<int32_t> tile_words = as_const((const int32_t*)p.tiles);
+#ifdef NANOCP_EXP_PRIO
+  if (wave >= W / 2) __builtin_amdgcn_s_setprio(NANOCP_EXP_PRIO);
+#endif
 
   // ---- per-lane constants of the LDS read patterns.  A row's 16-byte chunk c is stored at position
-  // c ^ (row & 15) (region A) or c ^ ((row >> 1) & 7) (region B).  For the rows a lane reads, the XOR mask is a
+  // c ^ (row & 15) (region A) or c ^ ((row >> 1) & 7) (rope region).  For the rows a lane reads, the XOR mask is a
   // per-lane constant, and the compile-time part of c only touches other bits, so a handful of precomputed
   // offsets plus immediates address everything.
   // K fragment (token block tb, k-step s): lane (r, g) reads token 16tb + r, chunk 4s+g:
   //   region A: r*1024 + (((s & 3) << 2) ^ g ^ r) * 16 + [16tb*1024 + (s >> 2)*256]
-  //   region B: r*128  + ((((s - 16) << 2) | g) ^ (r >> 1)) * 16 + [16tb*128]
+  //   rope:     r*128  + ((((s - 16) << 2) | g) ^ (r >> 1)) * 16 + [16tb*128]
   // V fragment (dim block dvb, tokens 32j + 16hf + 4g + 0..3): lane r supplies token row 4g + (r >> 2) (+32j+16hf),
   //   8 bytes at chunk 2dvb + ((r & 3) >> 1), half (r & 1):
   //   (4g + (r >> 2))*1024 + ((((dvb & 7) << 1) ^ x) * 16) + (r & 1)*8 + [(32j+16hf)*1024 + (dvb >> 3)*256],
   //   x = ((r & 3) >> 1) ^ (4g + (r >> 2))
   // Because a 16-byte shift distributes over XOR, each family of offsets is one per-lane base XOR a small
   // compile-time constant: k = K0 ^ ((s & 3) << 6), kb = KB0 ^ ((s - 16) << 6), v = V0 ^ ((dvb & 7) << 5).
-  const uint32_t K0 = (uint32_t)(r * kRowA + ((g ^ r) << 4));
-  const uint32_t KB0 = (uint32_t)(kRegionA + r * kRowB + ((g ^ (r >> 1)) << 4));
-  uint32_t V0;
-  {
-    const int vrow = 4 * g + (r >> 2);
-    const int x = ((r & 3) >> 1) ^ vrow;
-    V0 = (uint32_t)(vrow * kRowA + (x << 4) + (r & 1) * 8);
-  }
-
-  // global-side lane offsets of the page copy: token row tok = w + 4j is stored with chunk l ^ (tok & 15) at
-  // position l (four masks per wavefront); the rope slabs of rows 8i..8i+7, i = 2w, 2w+1, with chunk
-  // (l & 7) ^ ((row >> 1) & 7)
-  // (the masks of rows w, w + kMlaWaves, ... differ only in the bits above log2(kMlaWaves): base XOR constant)
-  const uint32_t D0 = (uint32_t)((lane ^ wave) << 4);
-  uint32_t dma_slab[kSlabs];
-#pragma unroll
-  for (int a = 0; a < kSlabs; ++a) {
-    const int row = 8 * (kSlabs * wave + a) + (lane >> 3);
-    dma_slab[a] = (uint32_t)((lane >> 3) * kRowBytes + kRowA + (((lane & 7) ^ ((row >> 1) & 7)) * 16));
-  }
+  // The lane-dependent offsets below are recomputed from the lane id once per page (a dozen integer instructions
+  // against thousands of cycles of page time) instead of being kept in registers across the whole tile loop: with
+  // Q (72) and the accumulators (128) resident, the registers they would occupy are the ones that decide
+  // between no spills and spills in the page loop.  fresh() hands the lane id through an empty asm statement so
+  // that the compiler does not hoist the computations back out of the loop.
+  auto fresh = [&]() {
+    int l = lane;
+    asm volatile("" : "+v"(l));
+    return l;
+  };
   const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
 
   // plan image: the counts live on the device; an image of another kernel variant, or one with grouped final rows
@@ -173,91 +189,129 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         tile.n_parts = w[8], tile.slot_begin = w[9], tile.final_row = w[10], tile.lse_shard = w[11];
       }
       uint64_t clk0 = 0;
-      if (p.tile_clock && tid == 0) clk0 = wall_clock64();
+      if (p.tile_clock) clk0 = wall_clock64();
       const cptr<int32_t> bt = as_const(p.block_table + (size_t)tile.bt_row * p.max_blocks);
       const int tb = tile.tok_begin, te = tile.tok_end;
       const int pg0 = tb / kPS, pg1 = (te - 1) / kPS + 1;  // pages [pg0, pg1) of the row
 
-      // direct-to-LDS copy of one page; wavefront w brings token rows w, w+8, ... and one slab of the rope part.
-      // Written as inline assembly so that the compiler does not serialise these copies against the LDS reads
-      // of the page being computed (it cannot tell the two buffers apart); completion is awaited explicitly.
-      auto issue_page = [&](int pg, int buf) {
-        const int page = bt[pg];
-        const uint64_t src = (uint64_t)(uintptr_t)p.k_pool + (uint64_t)page * (kPS * kRowBytes);
-        const uint32_t dst = lds_base + (uint32_t)(buf * kBufBytes);
+      // direct-to-LDS copies of one page; wavefront w brings token rows w, w+W, ... of the V part and its slabs
+      // of the rope part.  Written as inline assembly so that the compiler does not serialise these copies
+      // against the LDS reads of the page being computed; completion is awaited explicitly.
+      // global-side lane offsets: token row tok = w + W*j is stored with chunk l ^ (tok & 15) at position l (the masks
+      // of rows w, w + W, ... differ only in the bits above log2(W): base XOR constant); the rope slabs of rows
+      // 8i..8i+7 with chunk (l & 7) ^ ((row >> 1) & 7)
+      auto issue_page_a = [&](int pg, int buf) {
+        const uint64_t src = (uint64_t)(uintptr_t)p.k_pool + (uint64_t)bt[pg] * (kPS * kRowBytes);
+        const uint32_t dst = lds_base + (uint32_t)(buf * kRegionA);
+        const uint32_t D0 = (uint32_t)((fresh() ^ wave) << 4);
 #pragma unroll
-        for (int j = 0; j < kPS / kMlaWaves; ++j) {
-          const int tok = wave + kMlaWaves * j;
-          dma16(src + (uint64_t)(tok * kRowBytes), D0 ^ (uint32_t)(((kMlaWaves * j) & 15) << 4), dst + (uint32_t)(tok * kRowA));
+        for (int j = 0; j < kPS / W; ++j) {
+          const int tok = wave + W * j;
+          dma16(src + (uint64_t)(tok * kRowBytes), D0 ^ (uint32_t)(((W * j) & 15) << 4), dst + (uint32_t)(tok * kRowA));
         }
+      };
+      auto issue_page_rope = [&](int pg) {
+        const uint64_t src = (uint64_t)(uintptr_t)p.k_pool + (uint64_t)bt[pg] * (kPS * kRowBytes);
+        const int l = fresh();
 #pragma unroll
-        for (int a = 0; a < kSlabs; ++a)
-          dma16(src + (uint64_t)(8 * (kSlabs * wave + a) * kRowBytes), dma_slab[a],
-                dst + (uint32_t)(kRegionA + (kSlabs * wave + a) * 1024));
+        for (int a = 0; a < kSlabs; ++a) {
+          const int row = 8 * (kSlabs * wave + a) + (l >> 3);
+          const uint32_t off = (uint32_t)((l >> 3) * kRowBytes + kRowA + (((l & 7) ^ ((row >> 1) & 7)) * 16));
+          dma16(src + (uint64_t)(8 * (kSlabs * wave + a) * kRowBytes), off,
+                lds_base + (uint32_t)(kOffRope + (kSlabs * wave + a) * 1024));
+        }
       };
 
-      // Q fragments of this wavefront's heads (B operand): lane (g, n = r) holds Q[16hb + n][dims 8(4s+g) .. +8]
-      bf16x8 qf[kHB][kSteps];
+      // Q fragments of this wavefront's heads (B operand): lane (g, n = r) holds Q[16w + n][dims 8(4s+g) .. +8]
+      bf16x8 qf[kSteps];
+      {
+        const char* qrow = (const char*)p.q + ((size_t)tile.q_row * kHq + 16 * wave + r) * (kDk * 2);
 #pragma unroll
-      for (int hb = 0; hb < kHB; ++hb) {
-        const char* qrow = (const char*)p.q + ((size_t)tile.q_row * kHq + 16 * (kHB * wave + hb) + r) * (kDk * 2);
-#pragma unroll
-        for (int s = 0; s < kSteps; ++s) qf[hb][s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + (4 * s + g) * 16));
+        for (int s = 0; s < kSteps; ++s) qf[s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + (4 * s + g) * 16));
       }
 
-      f32x4 acc[kHB][kDv / 16];
+      // accumulator of this wavefront's dims (16-dim blocks kDW*w .. kDW*w + kDW - 1) for all head blocks:
+      // acc[dl][hb][i] = O^T[dim 16(kDW*w + dl) + 4g + i][head 16hb + r], scaled by 2^kPShift and not yet normalised
+      f32x4 acc[kDW][W];
 #pragma unroll
-      for (int hb = 0; hb < kHB; ++hb)
+      for (int dl = 0; dl < kDW; ++dl)
 #pragma unroll
-        for (int j = 0; j < kDv / 16; ++j) acc[hb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-      float m_run[kHB], l_run[kHB];
-#pragma unroll
-      for (int hb = 0; hb < kHB; ++hb) m_run[hb] = -INFINITY, l_run[hb] = 0.f;
+        for (int hb = 0; hb < W; ++hb) acc[dl][hb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      float m_run = -INFINITY;  // integer-valued reference exponent (log2 domain) of head 16w + r, see kHeadroom
+      float l_run = 0.f;        // this lane's share of the running sum of probabilities (times 2^kPShift)
 
-      issue_page(pg0, 0);
+#ifdef NANOCP_EXP_PHASES
+      uint64_t phc[5] = {0, 0, 0, 0, 0};
+      uint64_t pht = __builtin_readcyclecounter();
+#define PH(k) { const uint64_t now_ = __builtin_readcyclecounter(); phc[k] += now_ - pht; pht = now_; }
+#else
+#define PH(k)
+#endif
+      // Q must count as arrived BEFORE the page loop: the compiler tracks its own global loads with the same counter
+      // the page copies use, and would otherwise wait inside the loop -- at each Q fragment's first use -- for "all
+      // but n outstanding loads", which there means: for the next page's copy.  Naming every fragment as an asm
+      // operand makes it place those waits here.
+#pragma unroll
+      for (int s = 0; s < kSteps; ++s) {
+        u32x4 t = __builtin_bit_cast(u32x4, qf[s]);
+        asm volatile("" : "+v"(t));
+        qf[s] = __builtin_bit_cast(bf16x8, t);
+      }
+      issue_page_a(pg0, 0);
+      issue_page_rope(pg0);
       for (int pg = pg0; pg < pg1; ++pg) {
         const int buf = (pg - pg0) & 1;
-        // this page's copy (issued one iteration ago, or before the loop) and, on the first page, Q have landed ...
+        // this page's copies (V part issued one iteration ago, rope part half an iteration ago, or both before the
+        // loop) and, on the first page, Q have landed ...
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        wg_barrier();  // ... in every wavefront
-        // start the next page's copy; it overlaps this page's compute (its buffer was released by the barrier
-        // that ended the previous iteration)
-        if (pg + 1 < pg1) issue_page(pg + 1, buf ^ 1);
-        const lds_ptr A = lds + buf * kBufBytes;
-        const uint32_t boff = (uint32_t)(buf * kBufBytes);
-        const uint32_t KA = K0 + boff, KBA = KB0 + boff, VA = V0 + boff;  // this buffer's lane bases
+        wg_barrier();  // ... in every wavefront; and every wavefront is done with the previous page
+        PH(0)
+        if (pg + 1 < pg1) issue_page_a(pg + 1, buf ^ 1);  // overlaps this page's compute
+        const uint32_t boff = (uint32_t)(buf * kRegionA);
+        // this page's lane bases (see the comment on the read patterns above)
+        const int lq = fresh();
+        const int rq = lq & 15, gq = lq >> 4;
+        const uint32_t KA = (uint32_t)(rq * kRowA + ((gq ^ rq) << 4)) + boff;
+        const uint32_t KBA = (uint32_t)(kOffRope + rq * kRowB + ((gq ^ (rq >> 1)) << 4));
+        const uint32_t PA = (uint32_t)(kOffP + lq * 16);  // probabilities: fragment (hb, j) of lane l at +((hb*2+j)*64)*16
         const int tok0 = pg * kPS;
         const bool ragged = tok0 < tb || tok0 + kPS > te;  // uniform
         if (ragged) {
           // token slots outside [tb, te) may hold NaN patterns: clear their V part so that 0 * V stays 0
+          u32x4 zero = {0, 0, 0, 0};
+          asm volatile("" : "+v"(zero));  // materialised here, not kept (and spilled) across the tile loop
 #pragma unroll
-          for (int pass = 0; pass < kPS / kMlaWaves; ++pass) {
-            const int row = pass * kMlaWaves + wave;
+          for (int pass = 0; pass < kPS / W; ++pass) {
+            const int row = pass * W + wave;
             const int tok = tok0 + row;
-            if (tok < tb || tok >= te) *(__attribute__((address_space(3))) u32x4*)(A + row * kRowA + lane * 16) = u32x4{0, 0, 0, 0};
+            if (tok < tb || tok >= te) *LDS_AS(u32x4, lds + boff + row * kRowA + lane * 16) = zero;
           }
           asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
           wg_barrier();
         }
 
-        // ---- scores S^T[16 tokens x 16 heads] for the 4 token blocks of the page (x kHB head blocks): independent
-        // accumulators, so consecutive matrix instructions do not wait for each other
-        f32x4 S[4][kHB];
+        // ---- scores S^T[16 tokens x 16 heads] for the 4 token blocks of the page: independent accumulators, so
+        // consecutive matrix instructions do not wait for each other
+        f32x4 S[4];
 #pragma unroll
-        for (int tbk = 0; tbk < 4; ++tbk)
+        for (int tbk = 0; tbk < 4; ++tbk) S[tbk] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // software pipeline over units u = (k-step s, token-block pair) of 2 fragments and 2 MFMAs: the fragments
+        // of unit u+kKD are read while the MFMAs of unit u run; scheduling barriers keep the compiler from hoisting
+        // all LDS reads to the top (register blow-up)
+        // the six XOR-ed lane bases of the page (everything else about a fragment's address is an immediate offset)
+        uint32_t kb[6];
 #pragma unroll
-          for (int hb = 0; hb < kHB; ++hb) S[tbk][hb] = f32x4{0.f, 0.f, 0.f, 0.f};
-        // software pipeline over units u = (k-step s, token-block pair) of 2 fragments and 2*kHB MFMAs: the
-        // fragments of unit u+kKD are read while the MFMAs of unit u run; scheduling barriers keep the compiler
-        // from hoisting all LDS reads to the top (register blow-up)
+        for (int x = 0; x < 4; ++x) kb[x] = KA ^ (uint32_t)(x << 6);
+        kb[4] = KBA;
+        kb[5] = KBA ^ 64u;
         auto load_k = [&](bf16x8* kf, int u) {
           const int s = u >> 1;
 #pragma unroll
           for (int t2 = 0; t2 < 2; ++t2) {
             const int tbk = 2 * (u & 1) + t2;
-            const lds_ptr kp = s < kStepsA ? lds + (KA ^ (uint32_t)((s & 3) << 6)) + (16 * tbk * kRowA + (s >> 2) * 256)
-                                           : lds + (KBA ^ (uint32_t)((s - kStepsA) << 6)) + 16 * tbk * kRowB;
-            kf[t2] = __builtin_bit_cast(bf16x8, *(__attribute__((address_space(3))) const u32x4*)kp);
+            const lds_ptr kp = s < kStepsA ? lds + kb[s & 3] + (16 * tbk * kRowA + (s >> 2) * 256)
+                                           : lds + kb[4 + (s - kStepsA)] + 16 * tbk * kRowB;
+            kf[t2] = __builtin_bit_cast(bf16x8, *LDS_AS(const u32x4, kp));
           }
         };
         {
@@ -270,140 +324,267 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-              for (int hb = 0; hb < kHB; ++hb)
-                S[2 * (u & 1) + t2][hb] = mfma16(kf[u % (kKD + 1)][t2], qf[hb][u >> 1], S[2 * (u & 1) + t2][hb]);
+              S[2 * (u & 1) + t2] = mfma_bf16(kf[u % (kKD + 1)][t2], qf[u >> 1], S[2 * (u & 1) + t2]);
             __builtin_amdgcn_sched_barrier(0);
           }
         }
-        // ---- online softmax (log2 domain); S[tbk][hb][i] is token tok0 + 16tbk + 4g + i, head 16hb + r
-        bf16x8 hi[kHB][2], lo[kHB][2];  // k-blocks j = 0, 1: tokens 32j + 16hf + 4g + i  <->  element 4hf + i
-#pragma unroll
-        for (int hb = 0; hb < kHB; ++hb) {
-          float y[16];
-          float mloc = -INFINITY;
-#pragma unroll
-          for (int tbk = 0; tbk < 4; ++tbk)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              float v = S[tbk][hb][i] * c_log2;
-              if (ragged) {
-                const int tok = tok0 + 16 * tbk + 4 * g + i;
-                v = (tok >= tb && tok < te) ? v : -INFINITY;
-              }
-              y[tbk * 4 + i] = v;
-              mloc = fmaxf(mloc, v);
-            }
-          mloc = xor_max(mloc);
-          const float m_new = fmaxf(m_run[hb], mloc);  // finite: every page of the tile holds a token of its range
-          if (__any(m_new > m_run[hb])) {
-            const float alpha = __builtin_amdgcn_exp2f(m_run[hb] - m_new);
-            l_run[hb] *= alpha;
-            // the accumulators live in accumulation registers the vector ALU cannot address: rescale them a few
-            // at a time so that the round trip needs only a few temporaries
-#pragma unroll
-            for (int j = 0; j < kDv / 16; ++j) {
-              acc[hb][j] *= alpha;
-              if ((j & 3) == 3) __builtin_amdgcn_sched_barrier(0);
-            }
-            m_run[hb] = m_new;
-          }
-          float psum = 0.f;
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            y[e] = __builtin_amdgcn_exp2f(y[e] - m_run[hb]);
-            psum += y[e];
-          }
-          l_run[hb] += psum;
-          split8(y, hi[hb][0], lo[hb][0]);
-          split8(y + 8, hi[hb][1], lo[hb][1]);
-        }
 
-        // ---- O^T += V^T P^T over units u = (dim block dvb, token half j): one fragment (two transpose reads) feeds
-        // 2*kHB MFMAs (hi and lo term of P); kVD fragments are kept in flight
-        auto load_v = [&](int u) {
-          const int dvb = u >> 1, j = u & 1;
+        PH(1)
+        // ---- online softmax of heads 16w + r (log2 domain, integer running maximum); S[tbk][i] is token
+        // tok0 + 16tbk + 4g + i.  The probabilities leave as fp16 B-operand fragments: token half j = 0, 1 holds
+        // tokens 32j + 16hf + 4g + i as element 4hf + i.
+        {
+          // Masked token slots get -2^30 (not -inf): the integer part of a score goes through a float -> int
+          // conversion below, and p = 2^(-2^30 - m) underflows to exactly 0.  (Scores are assumed to lie within
+          // +-2^30 in the log2 domain.)
+          if (ragged) {
+#pragma unroll
+            for (int tbk = 0; tbk < 4; ++tbk)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const int tok = tok0 + 16 * tbk + 4 * g + i;
+                S[tbk][i] = (tok >= tb && tok < te) ? S[tbk][i] : kMaskedScore;
+              }
+            asm volatile("" ::: "memory");  // keeps this a branch taken on ragged pages only, not 80 selects on every page
+          }
+          // maximum over the raw scores (the softmax scale is positive), scaled once
+          float mraw = fmaxf(fmaxf(S[0][0], S[0][1]), S[0][2]);
+          mraw = fmaxf(fmaxf(mraw, S[0][3]), S[1][0]);
+          mraw = fmaxf(fmaxf(mraw, S[1][1]), S[1][2]);
+          mraw = fmaxf(fmaxf(mraw, S[1][3]), S[2][0]);
+          mraw = fmaxf(fmaxf(mraw, S[2][1]), S[2][2]);
+          mraw = fmaxf(fmaxf(mraw, S[2][3]), S[3][0]);
+          mraw = fmaxf(fmaxf(mraw, S[3][1]), S[3][2]);
+          mraw = xor_max(fmaxf(mraw, S[3][3]));  // a real score: every page of the tile holds a token of its range
+          // the reference moves to the page's ceiling only if that lies more than kHeadroom above it
+          const float m_page = __builtin_ceilf(mraw * c_log2);
+          const float m_new = m_page > m_run + (float)kHeadroom ? m_page : m_run;
+          // rescale factor of everything accumulated so far: 2^(m_run - m_new), exact (0 on the first page)
+          const float alpha = __builtin_amdgcn_ldexpf(1.f, (int)fmaxf(m_run - m_new, -200.f));
+          m_run = m_new;
+          l_run *= alpha;
+          if (g == 0) *LDS_AS(float, lds + kOffAlpha + (r * 8 + wave) * 4) = alpha;
+          // p * 2^kPShift = 2^frac(y) * 2^(floor(y) - m + kPShift): the significand depends on the score alone
+          const int m_off = kPShift - (int)m_new;
+          // four elements at a time (scheduling barriers in between): the sixteen chains are independent, and left
+          // alone the scheduler interleaves them all, which costs more live registers than this kernel has
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            u32x4 frag;
+#pragma unroll
+            for (int q4 = 0; q4 < 2; ++q4) {
+              float pw[4];
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const float yv = S[2 * j + q4][i] * c_log2;
+                const float ex = __builtin_amdgcn_exp2f(__builtin_amdgcn_fractf(yv));
+                int fl;
+                asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(fl) : "v"(yv));  // floor(y) as an integer, one instruction
+                pw[i] = __builtin_amdgcn_ldexpf(ex, fl + m_off);
+              }
+              frag[2 * q4] = pack_f16(pw[0], pw[1]);
+              frag[2 * q4 + 1] = pack_f16(pw[2], pw[3]);
+              l_run += (pw[0] + pw[1]) + (pw[2] + pw[3]);  // sum of p * 2^kPShift before the fp16 rounding
+              __builtin_amdgcn_sched_barrier(0);
+            }
+            *LDS_AS(u32x4, lds + PA + (wave * 2 + j) * 1024) = frag;
+          }
+        }
+        uint32_t VA;
+        {
+          const int lv = fresh();
+          const int vrow = 4 * (lv >> 4) + ((lv & 15) >> 2);
+          const int x = ((lv & 3) >> 1) ^ vrow;
+          VA = (uint32_t)(vrow * kRowA + (x << 4) + (lv & 1) * 8) + boff;
+        }
+        // raw V^T fragment (bf16 bits): two transpose reads; widened to fp16 later, in place, so that all reads of a
+        // token half are in flight together (one LDS latency per half, not one per read)
+        uint32_t vb[kDW];  // XOR-ed lane base of each of this wavefront's dim blocks
+#pragma unroll
+        for (int dl = 0; dl < kDW; ++dl) vb[dl] = (VA ^ (uint32_t)(((kDW * wave + dl) & 7) << 5)) + (uint32_t)(((kDW * wave + dl) >> 3) * 256);
+        auto load_v_raw = [&](int dl, int j) {
           u32x4 vf;
 #pragma unroll
           for (int hf = 0; hf < 2; ++hf) {
-            const lds_ptr ap = lds + (VA ^ (uint32_t)((dvb & 7) << 5)) + ((32 * j + 16 * hf) * kRowA + (dvb >> 3) * 256);
-            const s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)ap);
+            const lds_ptr ap = lds + vb[dl] + (32 * j + 16 * hf) * kRowA;
+            const s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AS(s16x4, ap));
             const u32x2 t2 = __builtin_bit_cast(u32x2, t);
             vf[2 * hf] = t2[0];
             vf[2 * hf + 1] = t2[1];
           }
-          return __builtin_bit_cast(bf16x8, vf);
+          return vf;
+        };
+        // The first token half's V^T reads are requested BEFORE the barrier (V has been in LDS since the top of the
+        // iteration): their latency passes while this wavefront waits for the others.  LDS operations complete in
+        // order, so waiting until only those reads are outstanding means the probabilities have been written.
+        u32x4 raw[kDW];
+#pragma unroll
+        for (int dl = 0; dl < kDW; ++dl) raw[dl] = load_v_raw(dl, 0);
+        if (2 * kDW <= 15) asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(2 * kDW <= 15 ? 2 * kDW : 15) : "memory");
+        else asm volatile("s_waitcnt lgkmcnt(15)" ::: "memory");
+        PH(2)
+        wg_barrier();  // all probabilities and rescale factors of this page are in LDS; the rope part is free
+        PH(3)
+        if (pg + 1 < pg1) issue_page_rope(pg + 1);
+
+        // ---- rescale the accumulators if some head's maximum moved (rare after the first pages of a tile)
+        {
+          float al[W];
+#pragma unroll
+          for (int q4 = 0; q4 < W / 4; ++q4) {
+            const f32x4 a4 = *LDS_AS(const f32x4, lds + kOffAlpha + r * 32 + q4 * 16);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) al[4 * q4 + i] = a4[i];
+          }
+          bool moved = false;
+#pragma unroll
+          for (int hb = 0; hb < W; ++hb) moved |= al[hb] != 1.f;
+          if (__any(moved)) {
+#pragma unroll
+            for (int hb = 0; hb < W; ++hb) {
+#pragma unroll
+              for (int dl = 0; dl < kDW; ++dl) acc[dl][hb] *= al[hb];
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+        }
+
+        // ---- O^T += V^T P^T for this wavefront's dims and all heads.  Per token half j: kDW V^T fragments (two
+        // transpose reads each, widened to fp16 in registers), then one probability fragment per head block
+        // feeds kDW matrix instructions.
+        auto widen_v = [&](u32x4 raw) {
+          u32x4 o;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) o[i] = bf16x2_to_f16x2(raw[i]);
+          return __builtin_bit_cast(f16x8, o);
+        };
+        auto load_p = [&](int hb, int j) {
+          return __builtin_bit_cast(f16x8, *LDS_AS(const u32x4, lds + PA + (hb * 2 + j) * 1024));
         };
         {
-          constexpr int kUnits = 2 * (kDv / 16);
-          bf16x8 vfr[kVD + 1];
+          f16x8 pf[2];
+          pf[0] = load_p(0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          f16x8 vf[kDW];
 #pragma unroll
-          for (int u = 0; u < kVD; ++u) vfr[u] = load_v(u);
+          for (int dl = 0; dl < kDW; ++dl) vf[dl] = widen_v(raw[dl]);
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int u = 0; u < kUnits; ++u) {
-            if (u + kVD < kUnits) vfr[(u + kVD) % (kVD + 1)] = load_v(u + kVD);
+          for (int u = 0; u < 2 * W; ++u) {  // units (j, hb): one probability fragment feeds kDW matrix instructions
+            const int j = u / W, hb = u % W;
+            if (u + 1 < 2 * W) pf[(u + 1) & 1] = load_p((u + 1) % W, (u + 1) / W);
+            // the next half's raw V^T fragments are requested during this half's units: one per unit over the last
+            // kDW units (kDW < W), or kDW / W per unit
+            constexpr int kPerUnit = kDW >= W ? kDW / W : 1;
+            constexpr int kFirst = kDW >= W ? 0 : W - kDW;
+            if (j == 0 && hb >= kFirst) {
+#pragma unroll
+              for (int q = 0; q < kPerUnit; ++q) raw[(hb - kFirst) * kPerUnit + q] = load_v_raw((hb - kFirst) * kPerUnit + q, 1);
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int hb = 0; hb < kHB; ++hb) acc[hb][u >> 1] = mfma16(vfr[u % (kVD + 1)], hi[hb][u & 1], acc[hb][u >> 1]);
-#pragma unroll
-            for (int hb = 0; hb < kHB; ++hb) acc[hb][u >> 1] = mfma16(vfr[u % (kVD + 1)], lo[hb][u & 1], acc[hb][u >> 1]);
+            for (int dl = 0; dl < kDW; ++dl) acc[dl][hb] = mfma_f16(vf[dl], pf[u & 1], acc[dl][hb]);
             __builtin_amdgcn_sched_barrier(0);
+            if (u == W - 1) {
+#pragma unroll
+              for (int dl = 0; dl < kDW; ++dl) vf[dl] = widen_v(raw[dl]);
+              __builtin_amdgcn_sched_barrier(0);
+            }
           }
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        wg_barrier();  // the buffer may be overwritten by the copy issued at the top of the next iteration
+        PH(4)
+        // the barrier at the top of the next iteration (or the one below) releases this page's buffers
       }
+#ifdef NANOCP_EXP_PHASES
+      if (p.tile_clock && lane == 0 && (wave == 0 || wave == W - 1)) {
+        uint64_t* o = p.tile_clock + 16 * (size_t)ti + 8 * (wave ? 1 : 0);
+        for (int k = 0; k < 5; ++k) o[k] = phc[k];
+        o[5] = (uint64_t)(pg1 - pg0);
+        o[6] = wall_clock64() - clk0;
+      }
+#endif
 
-      // ---- write this wavefront's heads: normalised output rows and natural-log LSE
-      float* dst_o;
-      float* dst_l;
-      if (tile.dst >= 0) {
-        dst_o = p.ws_o + (size_t)tile.dst * kHq * kDv;
-        dst_l = p.ws_lse + (size_t)tile.dst * kHq;
-      } else {
-        dst_o = p.out_o + (size_t)tile.shard * kHq * kDv;
-        dst_l = p.out_lse + (size_t)tile.lse_shard * kHq;
+      // ---- tile epilogue: per-head maximum and sum go through LDS (every wavefront needs them for all heads)
+      wg_barrier();  // every wavefront is done with the last page: LDS may be reused, copies may start
+      {
+        const float l = xor_sum(l_run);
+        if (g == 0) {
+          *LDS_AS(float, lds + kOffM + (16 * wave + r) * 4) = m_run;
+          *LDS_AS(float, lds + kOffL + (16 * wave + r) * 4) = l;
+        }
       }
-      const bool fin = tile.dst < 0 && p.final_out && tile.final_row >= 0;  // the shard alone is an output row
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      wg_barrier();
+      float inv[W], lse[W];  // of head 16hb + r
 #pragma unroll
-      for (int hb = 0; hb < kHB; ++hb) {
-        const float l = xor_sum(l_run[hb]);
-        const float inv = 1.f / l;
-        const int head = 16 * (kHB * wave + hb) + r;
-        const float lse = (m_run[hb] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
-        if (g == 0) dst_l[head] = lse;
-        if (fin) {
-          // acc[hb][dvb][i] = dim 16dvb + 4g + i of that head
-          const size_t fo = ((size_t)tile.final_row * kHq + head) * kDv + 4 * g;
+      for (int hb = 0; hb < W; ++hb) {
+        const float m = *LDS_AS(const float, lds + kOffM + (16 * hb + r) * 4);
+        const float l = *LDS_AS(const float, lds + kOffL + (16 * hb + r) * 4);
+        inv[hb] = 1.f / l;  // the accumulators and l carry the same factor 2^kPShift
+        lse[hb] = (m - (float)kPShift + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+      }
+      const int dim0 = 16 * kDW * wave + 4 * g;  // first dim of acc[0][.][0]
+
+      // writes a finished row set (this wavefront's dims of all heads) in its final form or as fp32 partial rows
+      auto write_rows = [&](const f32x4 (&o)[kDW][W], const float (&sc)[W], const float (&ls)[W]) {
+        const bool fin = p.final_out && tile.final_row >= 0;
+        if (wave == 0 && g == 0) {
 #pragma unroll
-          for (int dvb = 0; dvb < kDv / 16; ++dvb) {
-            const f32x4 v = acc[hb][dvb] * inv;
-            const float v4[4] = {v[0], v[1], v[2], v[3]};
-            store_final<4>(p.final_out, fo + 16 * dvb, p.final_kind, p.out_inv_scale, v4);
-            if ((dvb & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+          for (int hb = 0; hb < W; ++hb) {
+            p.out_lse[(size_t)tile.lse_shard * kHq + 16 * hb + r] = ls[hb];
+            if (fin && p.final_lse) p.final_lse[(size_t)tile.final_row * kHq + 16 * hb + r] = ls[hb];
           }
-          if (g == 0 && p.final_lse) p.final_lse[(size_t)tile.final_row * kHq + head] = lse;
-        } else {
-          float* orow = dst_o + (size_t)head * kDv + 4 * g;  // acc[hb][dvb][i] = dim 16dvb + 4g + i of that head
+        }
 #pragma unroll
-          for (int dvb = 0; dvb < kDv / 16; ++dvb) {
-            *(f32x4*)(orow + 16 * dvb) = acc[hb][dvb] * inv;
-            if ((dvb & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        for (int hb = 0; hb < W; ++hb) {
+#pragma unroll
+          for (int dl = 0; dl < kDW; ++dl) {
+            const f32x4 v = o[dl][hb] * sc[hb];
+            const size_t col = (size_t)(16 * hb + r) * kDv + dim0 + 16 * dl;
+            if (fin) {
+              const float v4[4] = {v[0], v[1], v[2], v[3]};
+              store_final<4>(p.final_out, (size_t)tile.final_row * kHq * kDv + col, kOut, p.out_inv_scale, v4);
+            } else {
+              *(f32x4*)(p.out_o + (size_t)tile.shard * kHq * kDv + col) = v;
+            }
           }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      };
+
+      if (tile.dst < 0) {
+        write_rows(acc, inv, lse);
+      } else {
+        // one of several tiles: store the normalised partial in register order ([wave][dl][hb][lane] x 16 bytes, so
+        // every store covers 1 KB of contiguous memory) and its LSEs; mla_reduce_kernel combines them after this
+        // kernel (a partial is 256 KB: reduced by the workgroup that delivers the last tile, as the GQA kernels do
+        // with their 8 KB partials, every long request ended with one compute unit reading 1-3 MB alone)
+        float* dst = p.ws_o + (size_t)tile.dst * ((size_t)kHq * kDv) + (size_t)wave * (kDW * W * 256) + lane * 4;
+#pragma unroll
+        for (int dl = 0; dl < kDW; ++dl)
+#pragma unroll
+          for (int hb = 0; hb < W; ++hb) *(f32x4*)(dst + (dl * W + hb) * 256) = acc[dl][hb] * inv[hb];
+        if (wave == 0 && g == 0) {
+#pragma unroll
+          for (int hb = 0; hb < W; ++hb) p.ws_lse[(size_t)tile.dst * kHq + 16 * hb + r] = lse[hb];
         }
       }
 
+#ifndef NANOCP_EXP_PHASES
       if (p.tile_clock && tid == 0) {
         p.tile_clock[3 * (size_t)ti] = clk0;
         p.tile_clock[3 * (size_t)ti + 1] = wall_clock64();
         p.tile_clock[3 * (size_t)ti + 2] = blockIdx.x;
       }
+#endif
     }
     if (tid == 0) next_s = (int)gridDim.x + atomicAdd(&p.sync[0], 1);
     __syncthreads();
     chunk = __builtin_amdgcn_readfirstlane(next_s);
     __syncthreads();
   }
+  // the last workgroup to leave re-arms the queue for the next launch
   if (tid == 0) {
     const int done = atomicAdd(&p.sync[1], 1);
     if (done == (int)gridDim.x - 1) {
@@ -413,13 +594,78 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
   }
 }
 
-// 128 heads: two wavefronts per SIMD, 256 registers each
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void mla_mfma_kernel(KParams p) {
-  mla_mfma_body<8, 1, 2>(p);
+// LSE-combine of the tile partials of one segment (same operator as the Phase 4 merge), reading the partials in
+// the register order the tile kernel stored them in.  One thread per 16-byte unit; parts are taken 8 at a time with a
+// running maximum.  Segments without parts are shards without tokens: O = 0, LSE = -inf.
+template <int W, int kOut>
+__global__ __launch_bounds__(256) void mla_reduce_kernel(KParams p, const Seg* __restrict__ segs) {
+  constexpr int kHq = 16 * W, kDW = 32 / W;
+  if (p.header && (int)blockIdx.x >= p.header[1]) return;  // plan image: launched for the bucket's capacity
+  const Seg sg = segs[blockIdx.x];
+  const int u = blockIdx.y * 256 + threadIdx.x;  // unit ((wave * kDW + dl) * W + hb) * 64 + lane
+  const int lane = u & 63, hb = (u >> 6) % W, dl = ((u >> 6) / W) % kDW, wave = (u >> 6) / (W * kDW);
+  const int head = 16 * hb + (lane & 15), dim0 = 16 * (kDW * wave + dl) + 4 * (lane >> 4);
+  const size_t per_tile = (size_t)kHq * kDv;
+  float top = -INFINITY, tot = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 < sg.n_parts; k0 += 8) {
+    float li[8];
+    f32x4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const size_t slot = (size_t)(sg.slot_begin + min(k0 + j, sg.n_parts - 1));
+      li[j] = p.ws_lse[slot * kHq + head];
+      v[j] = *(const f32x4*)(p.ws_o + slot * per_tile + (size_t)u * 4);
+    }
+    float bm = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (k0 + j >= sg.n_parts) li[j] = -INFINITY;
+      bm = fmaxf(bm, li[j]);
+    }
+    const float nt = fmaxf(top, bm);  // finite: tile partials are never empty
+    const float sc = expf(top - nt);
+    tot *= sc;
+    acc *= sc;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bool live = li[j] != -INFINITY;
+      const float w = live ? expf(li[j] - nt) : 0.f;
+      tot += w;
+      if (live) acc += v[j] * w;
+    }
+    top = nt;
+  }
+  const bool empty = sg.n_parts == 0;
+  const float inv = empty ? 0.f : 1.f / tot;
+  const float lse = empty ? -INFINITY : top + logf(tot);
+  const bool fin = p.final_out && sg.final_row >= 0;
+  if (dim0 == 0) {
+    p.out_lse[(size_t)sg.shard * kHq + head] = lse;
+    if (fin && p.final_lse) p.final_lse[(size_t)sg.final_row * kHq + head] = lse;
+  }
+  const f32x4 o = acc * inv;
+  const size_t col = (size_t)head * kDv + dim0;
+  if (fin) {
+    const float o4[4] = {o[0], o[1], o[2], o[3]};
+    store_final<4>(p.final_out, (size_t)sg.final_row * kHq * kDv + col, kOut, p.out_inv_scale, o4);
+  } else {
+    *(f32x4*)(p.out_o + (size_t)sg.shard * kHq * kDv + col) = o;
+  }
 }
-// 64 heads: one wavefront per SIMD, 512 registers: the LDS reads run far ahead
+
+// 128 heads: two wavefronts per SIMD, 256 registers each
+template <int kOut>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void mla_mfma_kernel(KParams p) {
+#ifndef NANOCP_EXP_KD
+#define NANOCP_EXP_KD 1
+#endif
+  mla_mfma_body<8, NANOCP_EXP_KD, kOut>(p);
+}
+// 64 heads: one wavefront per SIMD, 512 registers: the LDS reads of the score product run further ahead
+template <int kOut>
 __global__ __launch_bounds__(256, 1) void mla64_mfma_kernel(KParams p) {
-  mla_mfma_body<4, kMla64KD, kMla64VD>(p);
+  mla_mfma_body<4, 2, kOut>(p);
 }
 
 // The dynamic-LDS limit is an attribute of the kernel on ONE device: it is raised once per device and kernel, with
@@ -428,7 +674,7 @@ template <typename K>
 hipError_t allow_big_lds(K kernel, int bytes, int slot) {
   constexpr int kMaxDevices = 64;
   static std::mutex mu;
-  static bool done[2][kMaxDevices] = {};
+  static bool done[6][kMaxDevices] = {};
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
@@ -442,21 +688,48 @@ hipError_t allow_big_lds(K kernel, int bytes, int slot) {
   return hipSuccess;
 }
 
-}  // namespace
-
-hipError_t launch_mla_mfma(const KParams& p, int num_blocks, hipStream_t st) {
+template <int kOut>
+hipError_t launch_out(const KParams& p, int num_blocks, hipStream_t st, int slot) {
   if (p.Hq == 128) {
-    const hipError_t attr = allow_big_lds(mla_mfma_kernel, 2 * kBufBytes, 0);
+    const hipError_t attr = allow_big_lds(mla_mfma_kernel<kOut>, kLdsBytes, slot);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL(mla_mfma_kernel, dim3(num_blocks), dim3(512), 2 * kBufBytes, st, p);
+    hipLaunchKernelGGL(mla_mfma_kernel<kOut>, dim3(num_blocks), dim3(512), kLdsBytes, st, p);
   } else if (p.Hq == 64) {
-    const hipError_t attr = allow_big_lds(mla64_mfma_kernel, 2 * kBufBytes, 1);
+    const hipError_t attr = allow_big_lds(mla64_mfma_kernel<kOut>, kLdsBytes, slot + 3);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL(mla64_mfma_kernel, dim3(num_blocks), dim3(256), 2 * kBufBytes, st, p);
+    hipLaunchKernelGGL(mla64_mfma_kernel<kOut>, dim3(num_blocks), dim3(256), kLdsBytes, st, p);
   } else {
     return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+template <int kOut>
+hipError_t launch_reduce_out(const KParams& p, const Seg* segs, int num_segs, hipStream_t st) {
+  if (p.Hq == 128)
+    hipLaunchKernelGGL((mla_reduce_kernel<8, kOut>), dim3(num_segs, 128 * kDv / 4 / 256), dim3(256), 0, st, p, segs);
+  else if (p.Hq == 64)
+    hipLaunchKernelGGL((mla_reduce_kernel<4, kOut>), dim3(num_segs, 64 * kDv / 4 / 256), dim3(256), 0, st, p, segs);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// the reduction that goes with the tile kernel's partial layout: `num_segs` segments (cut (shard, head-set)s and
+// shards without tokens)
+hipError_t launch_mla_reduce(const KParams& p, const Seg* segs, int num_segs, hipStream_t st) {
+  if (num_segs <= 0) return hipSuccess;
+  if (p.final_kind == NANOCP_BF16) return launch_reduce_out<NANOCP_BF16>(p, segs, num_segs, st);
+  if (p.final_kind == NANOCP_FP8_E4M3) return launch_reduce_out<NANOCP_FP8_E4M3>(p, segs, num_segs, st);
+  return launch_reduce_out<NANOCP_F32>(p, segs, num_segs, st);
+}
+
+hipError_t launch_mla_mfma(const KParams& p, int num_blocks, hipStream_t st) {
+  if (p.final_kind == NANOCP_BF16) return launch_out<NANOCP_BF16>(p, num_blocks, st, 0);
+  if (p.final_kind == NANOCP_FP8_E4M3) return launch_out<NANOCP_FP8_E4M3>(p, num_blocks, st, 1);
+  return launch_out<NANOCP_F32>(p, num_blocks, st, 2);
 }
 
 }  // namespace nanocp

@@ -189,7 +189,7 @@ nanocp_status nanocp_plan_create(const nanocp_attn_desc* desc, const nanocp_shar
     const int Hkv = desc->num_kv_heads;
     const int G = desc->num_q_heads / Hkv;
     p->dynamic = p->variant != kGeneric;
-    p->fused = p->variant == kGqaMfmaBf16 || p->variant == kGqaMfmaFp8;
+    p->fused = p->variant == kGqaMfmaBf16 || p->variant == kGqaMfmaFp8;  // reduce inside the tile kernel
     // An MLA tile is expensive (144 KB of Q in, a 256 KB partial out and back in through the reduction) and its
     // pages cost the same compute everywhere, so the queue is all equal chunks; the GQA kernels are bandwidth-bound
     // with timing that varies, so they keep a self-scheduled tail.  (Measured on the benchmark workloads.)

@@ -4,8 +4,9 @@ stored code = e4m3(value * (1 / out_scale)), round to nearest even, saturating, 
 Checked (i) against the format itself: the device encoder must agree bit for bit with the generators' numpy encoder
 on a dense set of values (every code, every rounding boundary and its float32 neighbours, the subnormal range, the
 saturating range); (ii) bit for bit against the same kernels' float32 rows pushed through that encoder (same
-arithmetic, one cast); (iii) against the float64 checker's exact attention quantised the same way, where a code may
-differ by one step only (the float32 result may sit on the other side of a rounding boundary)."""
+arithmetic, one cast); (iii) against the float64 checker's exact attention: the decoded fp8 value must lie within the
+parity bar of the attention result plus half an E4M3 step at that magnitude (relative 2^-4, or 2^-10 of the scale in
+the subnormal range)."""
 import numpy as np
 import pytest
 import torch
@@ -14,6 +15,7 @@ import oracle
 import paper_2605_21100_amd as nanocp
 import workloads as W
 from workloads import numfmt
+from parity import FP32_ABS, LOWP_REL
 from workloads.device import DeviceBatch
 
 pytestmark = pytest.mark.gpu
@@ -103,10 +105,17 @@ def test_fp8_final_rows_and_merge(cid, tile_tokens):
     f32, q8 = res[torch.float32], res[torch.uint8]
     inv = np.float32(1) / np.float32(out_scale)
     assert np.array_equal(q8, numfmt.f32_to_e4m3fn(f32 * inv)), "fp8 rows != encoder(f32 rows)"
+    got = oracle.E4M3FN_TABLE[q8] * out_scale                              # decoded with the checker's own table
+    if d.kv_dtype == "f32":
+        bar = np.full_like(ref_m, FP32_ABS)
+    else:
+        bar = LOWP_REL * np.abs(ref_m) + LOWP_REL * np.sqrt((ref_m ** 2).mean(axis=-1, keepdims=True))
+    half_step = np.maximum(2.0 ** -10, (np.abs(ref_m) + bar) / out_scale * 2.0 ** -4) * out_scale
+    assert np.all(np.abs(got - ref_m) <= bar + 1.001 * half_step), float((np.abs(got - ref_m) - bar - half_step).max())
+    # and most codes are exactly the checker's (a sanity check that the bound above is not what carries the test)
     want = numfmt.f32_to_e4m3fn((ref_m / out_scale).astype(np.float32))
-    step = np.abs(_ordered(q8) - _ordered(want))
-    assert step.max() <= 1, int(step.max())
-    assert (step != 0).mean() < 0.02, float((step != 0).mean())
+    big = np.abs(ref_m) / out_scale >= 2.0 ** -3
+    assert ((_ordered(q8) != _ordered(want)) & big).sum() <= 0.02 * big.sum()
     assert (q8 & 0x7F).max() <= 0x7E and (q8 & 0x7F).max() >= 0x70      # no NaN code; the scale uses the top binades
     db.plan.close()
 
