@@ -38,7 +38,9 @@
  *
  * Kernels.  Matrix-core (MFMA) tile kernels exist for exactly these shapes:
  *   GQA  q bf16, kv bf16 or fp8, Hq / Hkv = 16, Dk = Dv = 128, ps = 64      ("gqa_mfma_bf16", "gqa_mfma_fp8")
- *   MLA  q bf16, kv bf16, Hq = 128 or 64, Dk = 576, Dv = 512, ps = 64       ("mla_mfma_bf16")
+ *   MLA  q bf16, kv bf16, Hq = 128 or 64, Dk = 576, Dv = 512, ps = 64,      ("mla_mfma_bf16")
+ *        softmax_scale > 0 and finite.  This kernel multiplies P.V in fp16: latent values beyond fp16's range
+ *        (|v| > 65504) saturate, and scores are assumed to lie within +-2^30 / log2(e).
  * Every other supported shape (any head counts, Dk <= 576, Dv <= 512, any page size the layout admits, f32 / bf16 /
  * fp8 KV; fp8 MLA is not supported at all) runs a plain fp32 kernel ("generic") that is correct but orders of
  * magnitude slower; nanocp_plan_kernel tells which one a plan uses.

@@ -145,9 +145,6 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
 
   const cptr<int32_t> chunk_offsets = as_const(p.chunk_offsets);
   const cptr<int32_t> tile_words = as_const((const int32_t*)p.tiles);
-#ifdef NANOCP_EXP_PRIO
-  if (wave >= W / 2) __builtin_amdgcn_s_setprio(NANOCP_EXP_PRIO);
-#endif
 
   // ---- per-lane constants of the LDS read patterns.  A row's 16-byte chunk c is stored at position
   // c ^ (row & 15) (region A) or c ^ ((row >> 1) & 7) (rope region).  For the rows a lane reads, the XOR mask is a
@@ -240,13 +237,6 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
       float m_run = -INFINITY;  // integer-valued reference exponent (log2 domain) of head 16w + r, see kHeadroom
       float l_run = 0.f;        // this lane's share of the running sum of probabilities (times 2^kPShift)
 
-#ifdef NANOCP_EXP_PHASES
-      uint64_t phc[5] = {0, 0, 0, 0, 0};
-      uint64_t pht = __builtin_readcyclecounter();
-#define PH(k) { const uint64_t now_ = __builtin_readcyclecounter(); phc[k] += now_ - pht; pht = now_; }
-#else
-#define PH(k)
-#endif
       // Q must count as arrived BEFORE the page loop: the compiler tracks its own global loads with the same counter
       // the page copies use, and would otherwise wait inside the loop -- at each Q fragment's first use -- for "all
       // but n outstanding loads", which there means: for the next page's copy.  Naming every fragment as an asm
@@ -265,7 +255,6 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         // loop) and, on the first page, Q have landed ...
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         wg_barrier();  // ... in every wavefront; and every wavefront is done with the previous page
-        PH(0)
         if (pg + 1 < pg1) issue_page_a(pg + 1, buf ^ 1);  // overlaps this page's compute
         const uint32_t boff = (uint32_t)(buf * kRegionA);
         // this page's lane bases (see the comment on the read patterns above)
@@ -328,8 +317,6 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
             __builtin_amdgcn_sched_barrier(0);
           }
         }
-
-        PH(1)
         // ---- online softmax of heads 16w + r (log2 domain, integer running maximum); S[tbk][i] is token
         // tok0 + 16tbk + 4g + i.  The probabilities leave as fp16 B-operand fragments: token half j = 0, 1 holds
         // tokens 32j + 16hf + 4g + i as element 4hf + i.
@@ -422,9 +409,7 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         for (int dl = 0; dl < kDW; ++dl) raw[dl] = load_v_raw(dl, 0);
         if (2 * kDW <= 15) asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(2 * kDW <= 15 ? 2 * kDW : 15) : "memory");
         else asm volatile("s_waitcnt lgkmcnt(15)" ::: "memory");
-        PH(2)
         wg_barrier();  // all probabilities and rescale factors of this page are in LDS; the rope part is free
-        PH(3)
         if (pg + 1 < pg1) issue_page_rope(pg + 1);
 
         // ---- rescale the accumulators if some head's maximum moved (rare after the first pages of a tile)
@@ -493,17 +478,8 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
           }
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        PH(4)
         // the barrier at the top of the next iteration (or the one below) releases this page's buffers
       }
-#ifdef NANOCP_EXP_PHASES
-      if (p.tile_clock && lane == 0 && (wave == 0 || wave == W - 1)) {
-        uint64_t* o = p.tile_clock + 16 * (size_t)ti + 8 * (wave ? 1 : 0);
-        for (int k = 0; k < 5; ++k) o[k] = phc[k];
-        o[5] = (uint64_t)(pg1 - pg0);
-        o[6] = wall_clock64() - clk0;
-      }
-#endif
 
       // ---- tile epilogue: per-head maximum and sum go through LDS (every wavefront needs them for all heads)
       wg_barrier();  // every wavefront is done with the last page: LDS may be reused, copies may start
@@ -571,13 +547,11 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         }
       }
 
-#ifndef NANOCP_EXP_PHASES
       if (p.tile_clock && tid == 0) {
         p.tile_clock[3 * (size_t)ti] = clk0;
         p.tile_clock[3 * (size_t)ti + 1] = wall_clock64();
         p.tile_clock[3 * (size_t)ti + 2] = blockIdx.x;
       }
-#endif
     }
     if (tid == 0) next_s = (int)gridDim.x + atomicAdd(&p.sync[0], 1);
     __syncthreads();
@@ -657,10 +631,7 @@ __global__ __launch_bounds__(256) void mla_reduce_kernel(KParams p, const Seg* _
 // 128 heads: two wavefronts per SIMD, 256 registers each
 template <int kOut>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void mla_mfma_kernel(KParams p) {
-#ifndef NANOCP_EXP_KD
-#define NANOCP_EXP_KD 1
-#endif
-  mla_mfma_body<8, NANOCP_EXP_KD, kOut>(p);
+  mla_mfma_body<8, 1, kOut>(p);
 }
 // 64 heads: one wavefront per SIMD, 512 registers: the LDS reads of the score product run further ahead
 template <int kOut>

@@ -52,7 +52,8 @@ int nanocp::pick_variant(const nanocp_attn_desc& d) {
     if (d.kv_dtype == NANOCP_FP8_E4M3 && d.page_size == 64) return kGqaMfmaFp8;
   }
   if (d.kind == NANOCP_MLA && d.q_dtype == NANOCP_BF16 && d.kv_dtype == NANOCP_BF16 && (d.num_q_heads == 128 || d.num_q_heads == 64) &&
-      d.head_dim_qk == 576 && d.head_dim_v == 512 && d.page_size == 64)
+      d.head_dim_qk == 576 && d.head_dim_v == 512 && d.page_size == 64 &&
+      d.softmax_scale > 0.f && d.softmax_scale < 3.0e38f)  // the kernel takes maxima over unscaled scores
     return kMlaMfmaBf16;
   return kGeneric;
 }
