@@ -73,7 +73,9 @@ constexpr int kOffP = kOffRope + kPS * kRowB;           // 139264, up to 16 KB: 
 constexpr int kOffAlpha = kOffP + 8 * 2 * 1024;         // [16 r][8 hb] floats: this page's accumulator rescale factors
 constexpr int kOffM = kOffAlpha + 512;                  // [128] per-head running maximum (tile end)
 constexpr int kOffL = kOffM + 512;                      // [128] per-head sum of probabilities (tile end)
-constexpr int kLdsBytes = kOffL + 512;                  // 157184
+constexpr int kOffMoved = kOffL + 512;                  // [2] per page parity: some head's reference moved on that page
+constexpr int kOffNext = kOffMoved + 8;                 // next work-queue entry, broadcast to the workgroup
+constexpr int kLdsBytes = kOffMoved + 16;               // 157200
 
 template <typename T>
 using cptr = const __attribute__((address_space(4))) T*;
@@ -110,13 +112,19 @@ __device__ inline uint32_t pack_f16(float a, float b) {
 }
 // Butterfly over the four 16-lane rows of a wavefront (lanes l, l^16, l^32, l^48 hold the same head) with the
 // row-swap instructions of the vector ALU (v_permlane16_swap / v_permlane32_swap) -- no trip through LDS.
+// (the maxima are written as instructions: fmaxf() on values that come out of a bit cast first spends an
+// instruction per operand on quieting NaNs)
+__device__ inline float max_raw(uint32_t a, uint32_t b) {
+  float o;
+  asm("v_max_f32 %0, %1, %2" : "=v"(o) : "v"(a), "v"(b));
+  return o;
+}
 __device__ inline float xor_max(float v) {
   const uint32_t u = __float_as_uint(v);
   const u32x2 a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-  const float w = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
-  const uint32_t uw = __float_as_uint(w);
+  const uint32_t uw = __float_as_uint(max_raw(a[0], a[1]));
   const u32x2 b = __builtin_amdgcn_permlane32_swap(uw, uw, false, false);
-  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+  return max_raw(b[0], b[1]);
 }
 __device__ inline float xor_sum(float v) {
   const uint32_t u = __float_as_uint(v);
@@ -133,8 +141,8 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
   constexpr int kHq = 16 * W;        // query heads = head blocks of 16 x W
   constexpr int kDW = 32 / W;        // 16-dim blocks of V one wavefront owns (4 or 8)
   constexpr int kSlabs = 8 / W;      // rope slabs (8 rows each) one wavefront copies
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  __shared__ int next_s;
+  extern __shared__ __attribute__((aligned(16))) char smem[];  // the only LDS object: its offset is 0, so LDS
+                                                               // addresses are plain lane offsets plus immediates
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -170,6 +178,13 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
     return l;
   };
   const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+  // a zero the compiler cannot trace back to a constant it already holds somewhere (which here would be a register
+  // that lives, spilled, across the whole tile loop)
+  auto fresh_zero = [] {
+    uint32_t z;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+    return z;
+  };
 
   // plan image: the counts live on the device; an image of another kernel variant, or one with grouped final rows
   // but no final output, is not run
@@ -256,6 +271,9 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         wg_barrier();  // ... in every wavefront; and every wavefront is done with the previous page
         if (pg + 1 < pg1) issue_page_a(pg + 1, buf ^ 1);  // overlaps this page's compute
+        // re-arm the other parity's "a reference moved" flag (last read during the previous page's P.V).  The flag is
+        // a shortcut only: set means "read the rescale factors", and they are written on every page.
+        if (tid == 0) *LDS_AS(uint32_t, lds + kOffMoved + (buf ^ 1) * 4) = fresh_zero();
         const uint32_t boff = (uint32_t)(buf * kRegionA);
         // this page's lane bases (see the comment on the read patterns above)
         const int lq = fresh();
@@ -267,8 +285,8 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         const bool ragged = tok0 < tb || tok0 + kPS > te;  // uniform
         if (ragged) {
           // token slots outside [tb, te) may hold NaN patterns: clear their V part so that 0 * V stays 0
-          u32x4 zero = {0, 0, 0, 0};
-          asm volatile("" : "+v"(zero));  // materialised here, not kept (and spilled) across the tile loop
+          const uint32_t z = fresh_zero();  // materialised here, not kept (and spilled) across the tile loop
+          const u32x4 zero = {z, z, z, z};
 #pragma unroll
           for (int pass = 0; pass < kPS / W; ++pass) {
             const int row = pass * W + wave;
@@ -351,30 +369,43 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
           m_run = m_new;
           l_run *= alpha;
           if (g == 0) *LDS_AS(float, lds + kOffAlpha + (r * 8 + wave) * 4) = alpha;
-          // p * 2^kPShift = 2^frac(y) * 2^(floor(y) - m + kPShift): the significand depends on the score alone
-          const int m_off = kPShift - (int)m_new;
+          if (__any(alpha != 1.f) && lane == 0) *LDS_AS(int, lds + kOffMoved + buf * 4) = 1;
+          // p * 2^kPShift = 2^frac(y) * 2^(floor(y) - m + kPShift): the significand depends on the score alone.
+          // While every reference of this wavefront lies in [-100, 118] (any sane input) that is exp2(y) * 2^(kPShift -
+          // m) with the hardware's exp2 over its normal range -- three instructions per score instead of six; scores
+          // below -126 then give 0 instead of at most 2^-20 of the reference.  Outside it the general form runs.
+          int m_off = kPShift - (int)m_new;
+          asm volatile("" : "+v"(m_off));  // one integer, not re-associated into the sixteen sums below
+          const bool plain = __all(m_new >= -100.f && m_new <= 118.f);
           // four elements at a time (scheduling barriers in between): the sixteen chains are independent, and left
           // alone the scheduler interleaves them all, which costs more live registers than this kernel has
+          auto emit = [&](auto&& prob) {
 #pragma unroll
-          for (int j = 0; j < 2; ++j) {
-            u32x4 frag;
+            for (int j = 0; j < 2; ++j) {
+              u32x4 frag;
 #pragma unroll
-            for (int q4 = 0; q4 < 2; ++q4) {
-              float pw[4];
+              for (int q4 = 0; q4 < 2; ++q4) {
+                float pw[4];
 #pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                const float yv = S[2 * j + q4][i] * c_log2;
-                const float ex = __builtin_amdgcn_exp2f(__builtin_amdgcn_fractf(yv));
-                int fl;
-                asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(fl) : "v"(yv));  // floor(y) as an integer, one instruction
-                pw[i] = __builtin_amdgcn_ldexpf(ex, fl + m_off);
+                for (int i = 0; i < 4; ++i) pw[i] = prob(S[2 * j + q4][i] * c_log2);
+                frag[2 * q4] = pack_f16(pw[0], pw[1]);
+                frag[2 * q4 + 1] = pack_f16(pw[2], pw[3]);
+                l_run += (pw[0] + pw[1]) + (pw[2] + pw[3]);  // sum of p * 2^kPShift before the fp16 rounding
+                __builtin_amdgcn_sched_barrier(0);
               }
-              frag[2 * q4] = pack_f16(pw[0], pw[1]);
-              frag[2 * q4 + 1] = pack_f16(pw[2], pw[3]);
-              l_run += (pw[0] + pw[1]) + (pw[2] + pw[3]);  // sum of p * 2^kPShift before the fp16 rounding
-              __builtin_amdgcn_sched_barrier(0);
+              *LDS_AS(u32x4, lds + PA + (wave * 2 + j) * 1024) = frag;
             }
-            *LDS_AS(u32x4, lds + PA + (wave * 2 + j) * 1024) = frag;
+          };
+          if (plain) {
+            const float unit = __builtin_amdgcn_ldexpf(1.f, m_off);
+            emit([&](float yv) { return __builtin_amdgcn_exp2f(yv) * unit; });
+          } else {
+            emit([&](float yv) {
+              const float ex = __builtin_amdgcn_exp2f(__builtin_amdgcn_fractf(yv));
+              int fl;
+              asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(fl) : "v"(yv));  // floor(y) as an integer, one instruction
+              return __builtin_amdgcn_ldexpf(ex, fl + m_off);
+            });
           }
         }
         uint32_t VA;
@@ -388,7 +419,10 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         // token half are in flight together (one LDS latency per half, not one per read)
         uint32_t vb[kDW];  // XOR-ed lane base of each of this wavefront's dim blocks
 #pragma unroll
-        for (int dl = 0; dl < kDW; ++dl) vb[dl] = (VA ^ (uint32_t)(((kDW * wave + dl) & 7) << 5)) + (uint32_t)(((kDW * wave + dl) >> 3) * 256);
+        for (int dl = 0; dl < kDW; ++dl) {
+          vb[dl] = (VA ^ (uint32_t)(((kDW * wave + dl) & 7) << 5)) + (uint32_t)(((kDW * wave + dl) >> 3) * 256);
+          asm volatile("" : "+v"(vb[dl]));  // a finished base: the token offsets below stay instruction immediates
+        }
         auto load_v_raw = [&](int dl, int j) {
           u32x4 vf;
 #pragma unroll
@@ -412,8 +446,8 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         wg_barrier();  // all probabilities and rescale factors of this page are in LDS; the rope part is free
         if (pg + 1 < pg1) issue_page_rope(pg + 1);
 
-        // ---- rescale the accumulators if some head's maximum moved (rare after the first pages of a tile)
-        {
+        // ---- rescale the accumulators if some head's reference moved (rare after the first pages of a tile)
+        if (__builtin_amdgcn_readfirstlane(*LDS_AS(const int, lds + kOffMoved + buf * 4))) {
           float al[W];
 #pragma unroll
           for (int q4 = 0; q4 < W / 4; ++q4) {
@@ -421,16 +455,11 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) al[4 * q4 + i] = a4[i];
           }
-          bool moved = false;
 #pragma unroll
-          for (int hb = 0; hb < W; ++hb) moved |= al[hb] != 1.f;
-          if (__any(moved)) {
+          for (int hb = 0; hb < W; ++hb) {
 #pragma unroll
-            for (int hb = 0; hb < W; ++hb) {
-#pragma unroll
-              for (int dl = 0; dl < kDW; ++dl) acc[dl][hb] *= al[hb];
-              __builtin_amdgcn_sched_barrier(0);
-            }
+            for (int dl = 0; dl < kDW; ++dl) acc[dl][hb] *= al[hb];
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
 
@@ -553,9 +582,9 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         p.tile_clock[3 * (size_t)ti + 2] = blockIdx.x;
       }
     }
-    if (tid == 0) next_s = (int)gridDim.x + atomicAdd(&p.sync[0], 1);
+    if (tid == 0) *LDS_AS(int, lds + kOffNext) = (int)gridDim.x + atomicAdd(&p.sync[0], 1);
     __syncthreads();
-    chunk = __builtin_amdgcn_readfirstlane(next_s);
+    chunk = __builtin_amdgcn_readfirstlane(*LDS_AS(const int, lds + kOffNext));
     __syncthreads();
   }
   // the last workgroup to leave re-arms the queue for the next launch
