@@ -91,6 +91,17 @@ __device__ inline void dma16(uint64_t base, uint32_t lane_off, uint32_t lds_addr
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_addr)
                : "memory");
 }
+// the same under a wavefront-uniform condition without a branch (a branch in the middle of the score product costs the
+// register allocator more than it saves): `live` is 1 or 0; with no lane enabled the copy is not issued
+__device__ inline void dma16_if(int live, uint64_t base, uint32_t lane_off, uint32_t lds_addr) {
+  uint64_t saved;
+  asm volatile(
+      "s_mov_b32 m0, %4\n\tv_cmp_ne_u32 vcc, 0, %1\n\ts_mov_b64 %0, exec\n\ts_and_b64 exec, exec, vcc\n\t"
+      "global_load_lds_dwordx4 %2, %3\n\ts_mov_b64 exec, %0"
+      : "=&s"(saved)
+      : "v"(live), "v"(lane_off), "s"(base), "s"(lds_addr)
+      : "memory", "scc", "vcc");
+}
 // workgroup barrier without the memory fences of __syncthreads(): copies in flight stay in flight
 __device__ inline void wg_barrier() { __builtin_amdgcn_s_barrier(); }
 
@@ -212,14 +223,23 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
       // global-side lane offsets: token row tok = w + W*j is stored with chunk l ^ (tok & 15) at position l (the masks
       // of rows w, w + W, ... differ only in the bits above log2(W): base XOR constant); the rope slabs of rows
       // 8i..8i+7 with chunk (l & 7) ^ ((row >> 1) & 7)
-      auto issue_page_a = [&](int pg, int buf) {
-        const uint64_t src = (uint64_t)(uintptr_t)p.k_pool + (uint64_t)bt[pg] * (kPS * kRowBytes);
-        const uint32_t dst = lds_base + (uint32_t)(buf * kRegionA);
-        const uint32_t D0 = (uint32_t)((fresh() ^ wave) << 4);
+      // The V-part copies of a page are NOT issued in one burst: the memory pipeline accepts only so many requests
+      // at a time, and a wavefront that issues kPS / W one-kilobyte copies back to back sits blocked at the issue
+      // for thousands of cycles (measured) with its matrix instructions waiting behind them.  They are handed
+      // out one at a time between the units of the score product instead (issue_a_row).
+      auto page_src = [&](int pg) { return (uint64_t)(uintptr_t)p.k_pool + (uint64_t)bt[pg] * (kPS * kRowBytes); };
+      auto issue_a_row = [&](int live, uint64_t src, int buf, int j) {
+        const int tok = wave + W * j;  // the lane offset is recomputed per copy (two instructions): no register held
+        dma16_if(live, src + (uint64_t)(tok * kRowBytes), (uint32_t)((fresh() ^ (tok & 15)) << 4),
+                 lds_base + (uint32_t)(buf * kRegionA) + (uint32_t)(tok * kRowA));
+      };
+      auto issue_page_a = [&](int pg, int buf) {  // a tile's first page: nothing to overlap with yet
+        const uint64_t src = page_src(pg);
 #pragma unroll
         for (int j = 0; j < kPS / W; ++j) {
           const int tok = wave + W * j;
-          dma16(src + (uint64_t)(tok * kRowBytes), D0 ^ (uint32_t)(((W * j) & 15) << 4), dst + (uint32_t)(tok * kRowA));
+          dma16(src + (uint64_t)(tok * kRowBytes), (uint32_t)((fresh() ^ (tok & 15)) << 4),
+                lds_base + (uint32_t)(buf * kRegionA) + (uint32_t)(tok * kRowA));
         }
       };
       auto issue_page_rope = [&](int pg) {
@@ -270,7 +290,9 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         // loop) and, on the first page, Q have landed ...
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         wg_barrier();  // ... in every wavefront; and every wavefront is done with the previous page
-        if (pg + 1 < pg1) issue_page_a(pg + 1, buf ^ 1);  // overlaps this page's compute
+        const bool more = pg + 1 < pg1;  // the next page's V part is copied under this page's score product
+        const uint64_t next_src = page_src(more ? pg + 1 : pg);
+        const int next_live = more ? 1 : 0;
         // re-arm the other parity's "a reference moved" flag (last read during the previous page's P.V).  The flag is
         // a shortcut only: set means "read the rescale factors", and they are written on every page.
         if (tid == 0) *LDS_AS(uint32_t, lds + kOffMoved + (buf ^ 1) * 4) = fresh_zero();
@@ -328,6 +350,8 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
 #pragma unroll
           for (int u = 0; u < 2 * kSteps; ++u) {
             if (u + kKD < 2 * kSteps) load_k(kf[(u + kKD) % (kKD + 1)], u + kKD);
+            constexpr int kEvery = 2 * kSteps / (kPS / W);  // units per copy: 36 units, 8 or 16 copies
+            if (u % kEvery == 0 && u / kEvery < kPS / W) issue_a_row(next_live, next_src, buf ^ 1, u / kEvery);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t2 = 0; t2 < 2; ++t2)
