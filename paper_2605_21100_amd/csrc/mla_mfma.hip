@@ -31,6 +31,7 @@
 #include <hip/hip_runtime.h>
 
 #include <mutex>
+#include <type_traits>
 
 #include "epilogue.h"
 #include "plan.h"
@@ -91,17 +92,6 @@ __device__ inline void dma16(uint64_t base, uint32_t lane_off, uint32_t lds_addr
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_addr)
                : "memory");
 }
-// the same under a wavefront-uniform condition without a branch (a branch in the middle of the score product costs the
-// register allocator more than it saves): `live` is 1 or 0; with no lane enabled the copy is not issued
-__device__ inline void dma16_if(int live, uint64_t base, uint32_t lane_off, uint32_t lds_addr) {
-  uint64_t saved;
-  asm volatile(
-      "s_mov_b32 m0, %4\n\tv_cmp_ne_u32 vcc, 0, %1\n\ts_mov_b64 %0, exec\n\ts_and_b64 exec, exec, vcc\n\t"
-      "global_load_lds_dwordx4 %2, %3\n\ts_mov_b64 exec, %0"
-      : "=&s"(saved)
-      : "v"(live), "v"(lane_off), "s"(base), "s"(lds_addr)
-      : "memory", "scc", "vcc");
-}
 // workgroup barrier without the memory fences of __syncthreads(): copies in flight stay in flight
 __device__ inline void wg_barrier() { __builtin_amdgcn_s_barrier(); }
 
@@ -145,13 +135,23 @@ __device__ inline float xor_sum(float v) {
   const u32x2 b = __builtin_amdgcn_permlane32_swap(uw, uw, false, false);
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
-// W wavefronts: 8 for 128 query heads (DeepSeek-V3-like), 4 for 64 (Kimi-K2-like).
+// W computing wavefronts: 8 for 128 query heads (DeepSeek-V3-like), 4 for 64 (Kimi-K2-like); the workgroup always has
+// 8 wavefronts.  Who issues the page copies matters: the memory pipeline takes a one-kilobyte direct-to-LDS copy only
+// every hundred-odd cycles, a wavefront that issues the next one earlier sits blocked at the issue, and everything
+// behind it in program order -- its matrix instructions -- waits too (measured: 16 copies in front of a 72-instruction
+// score product tripled its duration).  So the copies belong to wavefronts that can afford to block:
+//   64 heads:  wavefronts 4..7 do nothing else (they need no registers to speak of and spend their time blocked or
+//              at the barriers); the four computing wavefronts never touch global memory inside the page loop;
+//   128 heads: all 8 wavefronts compute, two per SIMD, and the hardware favours the older one of a pair, which then
+//              waits at each barrier for the younger one.  Wavefronts 0..3 (the older ones) issue all copies, one
+//              between every two units of their score product: their blocked time comes out of that slack and leaves
+//              the SIMD to the younger wavefront.
 // kKD: how many score-product units (two K fragments each) the LDS reads run ahead of the matrix instructions.
 template <int W, int kKD, int kOut>
 __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
   constexpr int kHq = 16 * W;        // query heads = head blocks of 16 x W
   constexpr int kDW = 32 / W;        // 16-dim blocks of V one wavefront owns (4 or 8)
-  constexpr int kSlabs = 8 / W;      // rope slabs (8 rows each) one wavefront copies
+  constexpr int kND = 4;             // copying wavefronts; each brings kPS / kND token rows and 8 / kND rope slabs
   extern __shared__ __attribute__((aligned(16))) char smem[];  // the only LDS object: its offset is 0, so LDS
                                                                // addresses are plain lane offsets plus immediates
 
@@ -161,6 +161,9 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
   const int r = lane & 15, g = lane >> 4;
   const float c_log2 = p.scale * 1.4426950408889634f;
   const lds_ptr lds = (lds_ptr)smem;
+  const bool computes = W == 8 || wave < W;          // wavefront-uniform
+  const bool copies = W == 8 ? wave < kND : wave >= W;
+  const int cw = W == 8 ? wave : wave - W;           // index among the copying wavefronts (if `copies`)
 
   const cptr<int32_t> chunk_offsets = as_const(p.chunk_offsets);
   const cptr<int32_t> tile_words = as_const((const int32_t*)p.tiles);
@@ -217,42 +220,53 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
       const int tb = tile.tok_begin, te = tile.tok_end;
       const int pg0 = tb / kPS, pg1 = (te - 1) / kPS + 1;  // pages [pg0, pg1) of the row
 
-      // direct-to-LDS copies of one page; wavefront w brings token rows w, w+W, ... of the V part and its slabs
-      // of the rope part.  Written as inline assembly so that the compiler does not serialise these copies
-      // against the LDS reads of the page being computed; completion is awaited explicitly.
-      // global-side lane offsets: token row tok = w + W*j is stored with chunk l ^ (tok & 15) at position l (the masks
-      // of rows w, w + W, ... differ only in the bits above log2(W): base XOR constant); the rope slabs of rows
-      // 8i..8i+7 with chunk (l & 7) ^ ((row >> 1) & 7)
-      // The V-part copies of a page are NOT issued in one burst: the memory pipeline accepts only so many requests
-      // at a time, and a wavefront that issues kPS / W one-kilobyte copies back to back sits blocked at the issue
-      // for thousands of cycles (measured) with its matrix instructions waiting behind them.  They are handed
-      // out one at a time between the units of the score product instead (issue_a_row).
+      // direct-to-LDS copies of one page; copying wavefront c brings token rows c, c + kND, ... of the V part and
+      // 8 / kND slabs (8 rows each) of the rope part.  Written as inline assembly so that the compiler does not
+      // serialise these copies against the LDS reads of the page being computed; completion is awaited explicitly.
+      // Global-side lane offsets: token row tok is stored with chunk l ^ (tok & 15) at position l; the rope slab of
+      // rows 8i..8i+7 with chunk (l & 7) ^ ((row >> 1) & 7).  The lane offset is recomputed per copy (two
+      // instructions) rather than held in a register.
       auto page_src = [&](int pg) { return (uint64_t)(uintptr_t)p.k_pool + (uint64_t)bt[pg] * (kPS * kRowBytes); };
-      auto issue_a_row = [&](int live, uint64_t src, int buf, int j) {
-        const int tok = wave + W * j;  // the lane offset is recomputed per copy (two instructions): no register held
-        dma16_if(live, src + (uint64_t)(tok * kRowBytes), (uint32_t)((fresh() ^ (tok & 15)) << 4),
-                 lds_base + (uint32_t)(buf * kRegionA) + (uint32_t)(tok * kRowA));
+      auto issue_a_row = [&](uint64_t src, int buf, int j) {
+        const int tok = cw + kND * j;
+        dma16(src + (uint64_t)(tok * kRowBytes), (uint32_t)((fresh() ^ (tok & 15)) << 4),
+              lds_base + (uint32_t)(buf * kRegionA) + (uint32_t)(tok * kRowA));
       };
-      auto issue_page_a = [&](int pg, int buf) {  // a tile's first page: nothing to overlap with yet
+      auto issue_page_a = [&](int pg, int buf) {  // all rows of this wavefront in one burst
         const uint64_t src = page_src(pg);
 #pragma unroll
-        for (int j = 0; j < kPS / W; ++j) {
-          const int tok = wave + W * j;
-          dma16(src + (uint64_t)(tok * kRowBytes), (uint32_t)((fresh() ^ (tok & 15)) << 4),
-                lds_base + (uint32_t)(buf * kRegionA) + (uint32_t)(tok * kRowA));
-        }
+        for (int j = 0; j < kPS / kND; ++j) issue_a_row(src, buf, j);
       };
       auto issue_page_rope = [&](int pg) {
-        const uint64_t src = (uint64_t)(uintptr_t)p.k_pool + (uint64_t)bt[pg] * (kPS * kRowBytes);
+        const uint64_t src = page_src(pg);
         const int l = fresh();
 #pragma unroll
-        for (int a = 0; a < kSlabs; ++a) {
-          const int row = 8 * (kSlabs * wave + a) + (l >> 3);
+        for (int a = 0; a < 8 / kND; ++a) {
+          const int slab = (8 / kND) * cw + a;
+          const int row = 8 * slab + (l >> 3);
           const uint32_t off = (uint32_t)((l >> 3) * kRowBytes + kRowA + (((l & 7) ^ ((row >> 1) & 7)) * 16));
-          dma16(src + (uint64_t)(8 * (kSlabs * wave + a) * kRowBytes), off,
-                lds_base + (uint32_t)(kOffRope + (kSlabs * wave + a) * 1024));
+          dma16(src + (uint64_t)(8 * slab * kRowBytes), off, lds_base + (uint32_t)(kOffRope + slab * 1024));
         }
       };
+
+      if (!computes) {
+        // a copying-only wavefront (64-head kernel): the same barriers as the computing ones, and the copies of the
+        // next page in between
+        issue_page_a(pg0, 0);
+        issue_page_rope(pg0);
+        for (int pg = pg0; pg < pg1; ++pg) {
+          const int tok0 = pg * kPS;
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          wg_barrier();                                        // top of the page
+          if (tok0 < tb || tok0 + kPS > te) wg_barrier();      // ragged page: after the clearing of unused rows
+          if (pg + 1 < pg1) issue_page_a(pg + 1, ((pg - pg0) & 1) ^ 1);
+          wg_barrier();                                        // probabilities written; the rope buffer is free
+          if (pg + 1 < pg1) issue_page_rope(pg + 1);
+        }
+        wg_barrier();  // the two barriers of the tile epilogue
+        wg_barrier();
+        continue;
+      }
 
       // Q fragments of this wavefront's heads (B operand): lane (g, n = r) holds Q[16w + n][dims 8(4s+g) .. +8]
       bf16x8 qf[kSteps];
@@ -282,29 +296,29 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         asm volatile("" : "+v"(t));
         qf[s] = __builtin_bit_cast(bf16x8, t);
       }
-      issue_page_a(pg0, 0);
-      issue_page_rope(pg0);
+      if (copies) {  // 128 heads: wavefronts 0..3
+        issue_page_a(pg0, 0);
+        issue_page_rope(pg0);
+      }
       for (int pg = pg0; pg < pg1; ++pg) {
         const int buf = (pg - pg0) & 1;
         // this page's copies (V part issued one iteration ago, rope part half an iteration ago, or both before the
         // loop) and, on the first page, Q have landed ...
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         wg_barrier();  // ... in every wavefront; and every wavefront is done with the previous page
-        const bool more = pg + 1 < pg1;  // the next page's V part is copied under this page's score product
-        const uint64_t next_src = page_src(more ? pg + 1 : pg);
-        const int next_live = more ? 1 : 0;
+        const bool more = pg + 1 < pg1;  // the next page is copied under this page's compute
+        const uint32_t boff = (uint32_t)(buf * kRegionA);
+        const int tok0 = pg * kPS;
+        const bool ragged = tok0 < tb || tok0 + kPS > te;  // uniform over the workgroup
         // re-arm the other parity's "a reference moved" flag (last read during the previous page's P.V).  The flag is
         // a shortcut only: set means "read the rescale factors", and they are written on every page.
         if (tid == 0) *LDS_AS(uint32_t, lds + kOffMoved + (buf ^ 1) * 4) = fresh_zero();
-        const uint32_t boff = (uint32_t)(buf * kRegionA);
         // this page's lane bases (see the comment on the read patterns above)
         const int lq = fresh();
         const int rq = lq & 15, gq = lq >> 4;
         const uint32_t KA = (uint32_t)(rq * kRowA + ((gq ^ rq) << 4)) + boff;
         const uint32_t KBA = (uint32_t)(kOffRope + rq * kRowB + ((gq ^ (rq >> 1)) << 4));
         const uint32_t PA = (uint32_t)(kOffP + lq * 16);  // probabilities: fragment (hb, j) of lane l at +((hb*2+j)*64)*16
-        const int tok0 = pg * kPS;
-        const bool ragged = tok0 < tb || tok0 + kPS > te;  // uniform
         if (ragged) {
           // token slots outside [tb, te) may hold NaN patterns: clear their V part so that 0 * V stays 0
           const uint32_t z = fresh_zero();  // materialised here, not kept (and spilled) across the tile loop
@@ -343,22 +357,27 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
             kf[t2] = __builtin_bit_cast(bf16x8, *LDS_AS(const u32x4, kp));
           }
         };
-        {
+        auto score_product = [&](auto with_copies) {
+          [[maybe_unused]] uint64_t next_src = 0;
+          if constexpr (with_copies.value) next_src = page_src(pg + 1);
           bf16x8 kf[kKD + 1][2];
 #pragma unroll
           for (int u = 0; u < kKD; ++u) load_k(kf[u], u);
 #pragma unroll
           for (int u = 0; u < 2 * kSteps; ++u) {
             if (u + kKD < 2 * kSteps) load_k(kf[(u + kKD) % (kKD + 1)], u + kKD);
-            constexpr int kEvery = 2 * kSteps / (kPS / W);  // units per copy: 36 units, 8 or 16 copies
-            if (u % kEvery == 0 && u / kEvery < kPS / W) issue_a_row(next_live, next_src, buf ^ 1, u / kEvery);
+            if constexpr (with_copies.value) {  // one row of the next page between every two units
+              if (u % 2 == 0 && u / 2 < kPS / kND) issue_a_row(next_src, buf ^ 1, u / 2);
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t2 = 0; t2 < 2; ++t2)
               S[2 * (u & 1) + t2] = mfma_bf16(kf[u % (kKD + 1)][t2], qf[u >> 1], S[2 * (u & 1) + t2]);
             __builtin_amdgcn_sched_barrier(0);
           }
-        }
+        };
+        if (W == 8 && copies && more) score_product(std::true_type{});
+        else score_product(std::false_type{});
         // ---- online softmax of heads 16w + r (log2 domain, integer running maximum); S[tbk][i] is token
         // tok0 + 16tbk + 4g + i.  The probabilities leave as fp16 B-operand fragments: token half j = 0, 1 holds
         // tokens 32j + 16hf + 4g + i as element 4hf + i.
@@ -441,17 +460,25 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         }
         // raw V^T fragment (bf16 bits): two transpose reads; widened to fp16 later, in place, so that all reads of a
         // token half are in flight together (one LDS latency per half, not one per read)
-        uint32_t vb[kDW];  // XOR-ed lane base of each of this wavefront's dim blocks
+        // XOR-ed lane base of each of this wavefront's dim blocks: held in registers (128 heads, 4 blocks), or
+        // rebuilt at each use (64 heads, 8 blocks: two instructions, and the registers are needed elsewhere)
+        constexpr bool kHoldBases = kDW <= 4;
+        auto v_base = [&](int dl) {
+          return (VA ^ (uint32_t)(((kDW * wave + dl) & 7) << 5)) + (uint32_t)(((kDW * wave + dl) >> 3) * 256);
+        };
+        uint32_t vb[kHoldBases ? kDW : 1];
+        if constexpr (kHoldBases) {
 #pragma unroll
-        for (int dl = 0; dl < kDW; ++dl) {
-          vb[dl] = (VA ^ (uint32_t)(((kDW * wave + dl) & 7) << 5)) + (uint32_t)(((kDW * wave + dl) >> 3) * 256);
-          asm volatile("" : "+v"(vb[dl]));  // a finished base: the token offsets below stay instruction immediates
+          for (int dl = 0; dl < kDW; ++dl) {
+            vb[dl] = v_base(dl);
+            asm volatile("" : "+v"(vb[dl]));  // a finished base: the token offsets below stay instruction immediates
+          }
         }
         auto load_v_raw = [&](int dl, int j) {
           u32x4 vf;
 #pragma unroll
           for (int hf = 0; hf < 2; ++hf) {
-            const lds_ptr ap = lds + vb[dl] + (32 * j + 16 * hf) * kRowA;
+            const lds_ptr ap = lds + (kHoldBases ? vb[kHoldBases ? dl : 0] : v_base(dl)) + (32 * j + 16 * hf) * kRowA;
             const s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_AS(s16x4, ap));
             const u32x2 t2 = __builtin_bit_cast(u32x2, t);
             vf[2 * hf] = t2[0];
@@ -462,13 +489,15 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         // The first token half's V^T reads are requested BEFORE the barrier (V has been in LDS since the top of the
         // iteration): their latency passes while this wavefront waits for the others.  LDS operations complete in
         // order, so waiting until only those reads are outstanding means the probabilities have been written.
-        u32x4 raw[kDW];
+        // dim blocks in flight: the wavefront's kDW blocks are taken kDB at a time (two with 64 heads: the
+        // registers four would take are not there)
+        constexpr int kDB = W == 8 ? 4 : 2;
+        u32x4 raw[kDB];
 #pragma unroll
-        for (int dl = 0; dl < kDW; ++dl) raw[dl] = load_v_raw(dl, 0);
-        if (2 * kDW <= 15) asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(2 * kDW <= 15 ? 2 * kDW : 15) : "memory");
-        else asm volatile("s_waitcnt lgkmcnt(15)" ::: "memory");
+        for (int dl = 0; dl < kDB; ++dl) raw[dl] = load_v_raw(dl, 0);
+        asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(2 * kDB) : "memory");
         wg_barrier();  // all probabilities and rescale factors of this page are in LDS; the rope part is free
-        if (pg + 1 < pg1) issue_page_rope(pg + 1);
+        if (W == 8 && copies && more) issue_page_rope(pg + 1);
 
         // ---- rescale the accumulators if some head's reference moved (rare after the first pages of a tile)
         if (__builtin_amdgcn_readfirstlane(*LDS_AS(const int, lds + kOffMoved + buf * 4))) {
@@ -499,33 +528,31 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         auto load_p = [&](int hb, int j) {
           return __builtin_bit_cast(f16x8, *LDS_AS(const u32x4, lds + PA + (hb * 2 + j) * 1024));
         };
-        {
+#pragma unroll
+        for (int dh = 0; dh < kDW / kDB; ++dh) {  // one pass (128 heads) or four (64 heads)
           f16x8 pf[2];
           pf[0] = load_p(0, 0);
           __builtin_amdgcn_sched_barrier(0);
-          f16x8 vf[kDW];
+          f16x8 vf[kDB];
 #pragma unroll
-          for (int dl = 0; dl < kDW; ++dl) vf[dl] = widen_v(raw[dl]);
+          for (int dl = 0; dl < kDB; ++dl) vf[dl] = widen_v(raw[dl]);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int u = 0; u < 2 * W; ++u) {  // units (j, hb): one probability fragment feeds kDW matrix instructions
+          for (int u = 0; u < 2 * W; ++u) {  // units (j, hb): one probability fragment feeds kDB matrix instructions
             const int j = u / W, hb = u % W;
             if (u + 1 < 2 * W) pf[(u + 1) & 1] = load_p((u + 1) % W, (u + 1) / W);
-            // the next half's raw V^T fragments are requested during this half's units: one per unit over the last
-            // kDW units (kDW < W), or kDW / W per unit
-            constexpr int kPerUnit = kDW >= W ? kDW / W : 1;
-            constexpr int kFirst = kDW >= W ? 0 : W - kDW;
-            if (j == 0 && hb >= kFirst) {
-#pragma unroll
-              for (int q = 0; q < kPerUnit; ++q) raw[(hb - kFirst) * kPerUnit + q] = load_v_raw((hb - kFirst) * kPerUnit + q, 1);
-            }
+            // the raw V^T fragments needed next (this pass's second token half, then the next pass's first) are
+            // requested during the current half's units, one per unit over its last kDB units
+            constexpr int kFirst = W - kDB;
+            const bool next_pass = j == 1 && dh + 1 < kDW / kDB;
+            if (hb >= kFirst && (j == 0 || next_pass)) raw[hb - kFirst] = load_v_raw(kDB * (dh + (j == 1 ? 1 : 0)) + hb - kFirst, j ^ 1);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int dl = 0; dl < kDW; ++dl) acc[dl][hb] = mfma_f16(vf[dl], pf[u & 1], acc[dl][hb]);
+            for (int dl = 0; dl < kDB; ++dl) acc[kDB * dh + dl][hb] = mfma_f16(vf[dl], pf[u & 1], acc[kDB * dh + dl][hb]);
             __builtin_amdgcn_sched_barrier(0);
-            if (u == W - 1) {
+            if (u == W - 1 || (u == 2 * W - 1 && dh + 1 < kDW / kDB)) {
 #pragma unroll
-              for (int dl = 0; dl < kDW; ++dl) vf[dl] = widen_v(raw[dl]);
+              for (int dl = 0; dl < kDB; ++dl) vf[dl] = widen_v(raw[dl]);
               __builtin_amdgcn_sched_barrier(0);
             }
           }
@@ -681,15 +708,15 @@ __global__ __launch_bounds__(256) void mla_reduce_kernel(KParams p, const Seg* _
   }
 }
 
-// 128 heads: two wavefronts per SIMD, 256 registers each
+// Both kernels: 8 wavefronts, two per SIMD, 256 registers each.  128 heads: all of them compute.
 template <int kOut>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void mla_mfma_kernel(KParams p) {
   mla_mfma_body<8, 1, kOut>(p);
 }
-// 64 heads: one wavefront per SIMD, 512 registers: the LDS reads of the score product run further ahead
+// 64 heads: four compute, four copy
 template <int kOut>
-__global__ __launch_bounds__(256, 1) void mla64_mfma_kernel(KParams p) {
-  mla_mfma_body<4, 2, kOut>(p);
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void mla64_mfma_kernel(KParams p) {
+  mla_mfma_body<4, 1, kOut>(p);
 }
 
 // The dynamic-LDS limit is an attribute of the kernel on ONE device: it is raised once per device and kernel, with
@@ -721,7 +748,7 @@ hipError_t launch_out(const KParams& p, int num_blocks, hipStream_t st, int slot
   } else if (p.Hq == 64) {
     const hipError_t attr = allow_big_lds(mla64_mfma_kernel<kOut>, kLdsBytes, slot + 3);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL(mla64_mfma_kernel<kOut>, dim3(num_blocks), dim3(256), kLdsBytes, st, p);
+    hipLaunchKernelGGL(mla64_mfma_kernel<kOut>, dim3(num_blocks), dim3(512), kLdsBytes, st, p);
   } else {
     return hipErrorInvalidValue;
   }
