@@ -155,9 +155,8 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
   extern __shared__ __attribute__((aligned(16))) char smem[];  // the only LDS object: its offset is 0, so LDS
                                                                // addresses are plain lane offsets plus immediates
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r = lane & 15, g = lane >> 4;
   const float c_log2 = p.scale * 1.4426950408889634f;
   const lds_ptr lds = (lds_ptr)smem;
@@ -271,9 +270,12 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
       // Q fragments of this wavefront's heads (B operand): lane (g, n = r) holds Q[16w + n][dims 8(4s+g) .. +8]
       bf16x8 qf[kSteps];
       {
-        const char* qrow = (const char*)p.q + ((size_t)tile.q_row * kHq + 16 * wave + r) * (kDk * 2);
+        // uniform base + 32-bit lane offset from a re-read lane id (see the note on output addresses below)
+        const char* qrows = (const char*)p.q + ((size_t)tile.q_row * kHq + 16 * wave) * (kDk * 2);
+        const int lq0 = fresh();
+        const uint32_t qoff = (uint32_t)((lq0 & 15) * (kDk * 2) + (lq0 >> 4) * 16);
 #pragma unroll
-        for (int s = 0; s < kSteps; ++s) qf[s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + (4 * s + g) * 16));
+        for (int s = 0; s < kSteps; ++s) qf[s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrows + (qoff + (uint32_t)(64 * s))));
       }
 
       // accumulator of this wavefront's dims (16-dim blocks kDW*w .. kDW*w + kDW - 1) for all head blocks:
@@ -312,7 +314,7 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         const bool ragged = tok0 < tb || tok0 + kPS > te;  // uniform over the workgroup
         // re-arm the other parity's "a reference moved" flag (last read during the previous page's P.V).  The flag is
         // a shortcut only: set means "read the rescale factors", and they are written on every page.
-        if (tid == 0) *LDS_AS(uint32_t, lds + kOffMoved + (buf ^ 1) * 4) = fresh_zero();
+        if (wave == 0 && fresh() == 0) *LDS_AS(uint32_t, lds + kOffMoved + (buf ^ 1) * 4) = fresh_zero();
         // this page's lane bases (see the comment on the read patterns above)
         const int lq = fresh();
         const int rq = lq & 15, gq = lq >> 4;
@@ -411,8 +413,9 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
           const float alpha = __builtin_amdgcn_ldexpf(1.f, (int)fmaxf(m_run - m_new, -200.f));
           m_run = m_new;
           l_run *= alpha;
-          if (g == 0) *LDS_AS(float, lds + kOffAlpha + (r * 8 + wave) * 4) = alpha;
-          if (__any(alpha != 1.f) && lane == 0) *LDS_AS(int, lds + kOffMoved + buf * 4) = 1;
+          const int la = fresh();  // (an address built from the kernel's lane constants would be kept across the tile loop)
+          if (la < 16) *LDS_AS(float, lds + kOffAlpha + (la * 8 + wave) * 4) = alpha;
+          if (__any(alpha != 1.f) && la == 0) *LDS_AS(int, lds + kOffMoved + buf * 4) = 1;
           // p * 2^kPShift = 2^frac(y) * 2^(floor(y) - m + kPShift): the significand depends on the score alone.
           // While every reference of this wavefront lies in [-100, 118] (any sane input) that is exp2(y) * 2^(kPShift -
           // m) with the hardware's exp2 over its normal range -- three instructions per score instead of six; scores
@@ -422,7 +425,7 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
           const bool plain = __all(m_new >= -100.f && m_new <= 118.f);
           // four elements at a time (scheduling barriers in between): the sixteen chains are independent, and left
           // alone the scheduler interleaves them all, which costs more live registers than this kernel has
-          auto emit = [&](auto&& prob) {
+          auto emit = [&](auto&& prob, auto fence_every_four) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
               u32x4 frag;
@@ -434,21 +437,22 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
                 frag[2 * q4] = pack_f16(pw[0], pw[1]);
                 frag[2 * q4 + 1] = pack_f16(pw[2], pw[3]);
                 l_run += (pw[0] + pw[1]) + (pw[2] + pw[3]);  // sum of p * 2^kPShift before the fp16 rounding
-                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (fence_every_four.value) __builtin_amdgcn_sched_barrier(0);
               }
               *LDS_AS(u32x4, lds + PA + (wave * 2 + j) * 1024) = frag;
+              __builtin_amdgcn_sched_barrier(0);
             }
           };
           if (plain) {
             const float unit = __builtin_amdgcn_ldexpf(1.f, m_off);
-            emit([&](float yv) { return __builtin_amdgcn_exp2f(yv) * unit; });
+            emit([&](float yv) { return __builtin_amdgcn_exp2f(yv) * unit; }, std::false_type{});
           } else {
             emit([&](float yv) {
               const float ex = __builtin_amdgcn_exp2f(__builtin_amdgcn_fractf(yv));
               int fl;
               asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(fl) : "v"(yv));  // floor(y) as an integer, one instruction
               return __builtin_amdgcn_ldexpf(ex, fl + m_off);
-            });
+            }, std::true_type{});
           }
         }
         uint32_t VA;
@@ -565,44 +569,59 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
       wg_barrier();  // every wavefront is done with the last page: LDS may be reused, copies may start
       {
         const float l = xor_sum(l_run);
-        if (g == 0) {
-          *LDS_AS(float, lds + kOffM + (16 * wave + r) * 4) = m_run;
-          *LDS_AS(float, lds + kOffL + (16 * wave + r) * 4) = l;
+        const int lw = fresh();
+        if (lw < 16) {
+          *LDS_AS(float, lds + kOffM + (16 * wave + lw) * 4) = m_run;
+          *LDS_AS(float, lds + kOffL + (16 * wave + lw) * 4) = l;
         }
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       wg_barrier();
+      // Addresses from here on are built from a lane id that is re-read here: a wavefront-uniform base pointer plus
+      // a 32-bit offset.  (Built from the kernel's lane constants, the addresses of all reads and stores below are
+      // hoisted out of the tile loop and kept -- spilled -- across it; a kernel with spills needs scratch memory,
+      // and a launch that needs scratch memory costs tens of microseconds more.)
+      const int le = fresh();
+      const int re = le & 15, ge = le >> 4;
       float inv[W], lse[W];  // of head 16hb + r
+      {
+        const uint32_t ml = (uint32_t)(kOffM + re * 4);
 #pragma unroll
-      for (int hb = 0; hb < W; ++hb) {
-        const float m = *LDS_AS(const float, lds + kOffM + (16 * hb + r) * 4);
-        const float l = *LDS_AS(const float, lds + kOffL + (16 * hb + r) * 4);
-        inv[hb] = 1.f / l;  // the accumulators and l carry the same factor 2^kPShift
-        lse[hb] = (m - (float)kPShift + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+        for (int hb = 0; hb < W; ++hb) {
+          const float m = *LDS_AS(const float, lds + ml + 64 * hb);
+          const float l = *LDS_AS(const float, lds + ml + (kOffL - kOffM) + 64 * hb);
+          inv[hb] = 1.f / l;  // the accumulators and l carry the same factor 2^kPShift
+          lse[hb] = (m - (float)kPShift + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+        }
       }
-      const int dim0 = 16 * kDW * wave + 4 * g;  // first dim of acc[0][.][0]
+      const uint32_t lane_col = (uint32_t)(re * kDv + 16 * kDW * wave + 4 * ge);  // head r, first dim of acc[0][.][0]
 
       // writes a finished row set (this wavefront's dims of all heads) in its final form or as fp32 partial rows
       auto write_rows = [&](const f32x4 (&o)[kDW][W], const float (&sc)[W], const float (&ls)[W]) {
         const bool fin = p.final_out && tile.final_row >= 0;
-        if (wave == 0 && g == 0) {
+        if (wave == 0 && ge == 0) {
+          float* lse_row = p.out_lse + (size_t)tile.lse_shard * kHq;
+          float* fin_lse_row = (fin && p.final_lse) ? p.final_lse + (size_t)tile.final_row * kHq : nullptr;
 #pragma unroll
           for (int hb = 0; hb < W; ++hb) {
-            p.out_lse[(size_t)tile.lse_shard * kHq + 16 * hb + r] = ls[hb];
-            if (fin && p.final_lse) p.final_lse[(size_t)tile.final_row * kHq + 16 * hb + r] = ls[hb];
+            lse_row[(uint32_t)(16 * hb + re)] = ls[hb];
+            if (fin_lse_row) fin_lse_row[(uint32_t)(16 * hb + re)] = ls[hb];
           }
         }
+        constexpr int kElem = kOut == NANOCP_F32 ? 4 : kOut == NANOCP_BF16 ? 2 : 1;
+        char* fin_row = fin ? (char*)p.final_out + (size_t)tile.final_row * kHq * kDv * kElem : nullptr;
+        float* part_row = p.out_o + (size_t)tile.shard * kHq * kDv;
 #pragma unroll
         for (int hb = 0; hb < W; ++hb) {
 #pragma unroll
           for (int dl = 0; dl < kDW; ++dl) {
             const f32x4 v = o[dl][hb] * sc[hb];
-            const size_t col = (size_t)(16 * hb + r) * kDv + dim0 + 16 * dl;
+            const uint32_t col = lane_col + (uint32_t)(16 * hb * kDv + 16 * dl);
             if (fin) {
               const float v4[4] = {v[0], v[1], v[2], v[3]};
-              store_final<4>(p.final_out, (size_t)tile.final_row * kHq * kDv + col, kOut, p.out_inv_scale, v4);
+              store_final<4>(fin_row, col, kOut, p.out_inv_scale, v4);
             } else {
-              *(f32x4*)(p.out_o + (size_t)tile.shard * kHq * kDv + col) = v;
+              *(f32x4*)(part_row + col) = v;
             }
           }
           __builtin_amdgcn_sched_barrier(0);
@@ -616,30 +635,32 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         // every store covers 1 KB of contiguous memory) and its LSEs; mla_reduce_kernel combines them after this
         // kernel (a partial is 256 KB: reduced by the workgroup that delivers the last tile, as the GQA kernels do
         // with their 8 KB partials, every long request ended with one compute unit reading 1-3 MB alone)
-        float* dst = p.ws_o + (size_t)tile.dst * ((size_t)kHq * kDv) + (size_t)wave * (kDW * W * 256) + lane * 4;
+        float* dst = p.ws_o + (size_t)tile.dst * ((size_t)kHq * kDv) + (size_t)wave * (kDW * W * 256);
+        const uint32_t lane4 = (uint32_t)le * 4;
 #pragma unroll
         for (int dl = 0; dl < kDW; ++dl)
 #pragma unroll
-          for (int hb = 0; hb < W; ++hb) *(f32x4*)(dst + (dl * W + hb) * 256) = acc[dl][hb] * inv[hb];
-        if (wave == 0 && g == 0) {
+          for (int hb = 0; hb < W; ++hb) *(f32x4*)(dst + (lane4 + (uint32_t)((dl * W + hb) * 256))) = acc[dl][hb] * inv[hb];
+        if (wave == 0 && ge == 0) {
+          float* lse_row = p.ws_lse + (size_t)tile.dst * kHq;
 #pragma unroll
-          for (int hb = 0; hb < W; ++hb) p.ws_lse[(size_t)tile.dst * kHq + 16 * hb + r] = lse[hb];
+          for (int hb = 0; hb < W; ++hb) lse_row[(uint32_t)(16 * hb + re)] = lse[hb];
         }
       }
 
-      if (p.tile_clock && tid == 0) {
+      if (p.tile_clock && wave == 0 && fresh() == 0) {
         p.tile_clock[3 * (size_t)ti] = clk0;
         p.tile_clock[3 * (size_t)ti + 1] = wall_clock64();
         p.tile_clock[3 * (size_t)ti + 2] = blockIdx.x;
       }
     }
-    if (tid == 0) *LDS_AS(int, lds + kOffNext) = (int)gridDim.x + atomicAdd(&p.sync[0], 1);
+    if (wave == 0 && fresh() == 0) *LDS_AS(int, lds + kOffNext) = (int)gridDim.x + atomicAdd(&p.sync[0], 1);
     __syncthreads();
     chunk = __builtin_amdgcn_readfirstlane(*LDS_AS(const int, lds + kOffNext));
     __syncthreads();
   }
   // the last workgroup to leave re-arms the queue for the next launch
-  if (tid == 0) {
+  if (wave == 0 && fresh() == 0) {
     const int done = atomicAdd(&p.sync[1], 1);
     if (done == (int)gridDim.x - 1) {
       p.sync[0] = 0;
