@@ -151,6 +151,46 @@ def quick_config(cid, steps, warmup):
     return res
 
 
+def time_kv_append(batch, db, workload):
+    """nanocp_kv_append (pure data movement) on the workload's shapes: (a) a decode step's append, one token per
+    shard entry at its last position; (b) a bulk append of up to 65536 tokens.  Payload rows are random bytes."""
+    import torch
+    import paper_2605_21100_amd as nanocp
+    d = batch.desc
+    mla = d.kind == "mla"
+    es = db.k_pool.element_size()
+    res = {"metric": "nanocp_kv_append", "workload": workload,
+           "kv_dtype": d.kv_dtype, "kind": d.kind}
+    last_rows = np.array([bt for _, bt, lo, hi in batch.shards if hi > lo], np.int32)
+    last_pos = np.array([hi - 1 for _, bt, lo, hi in batch.shards if hi > lo], np.int32)
+    rows, pos = [], []
+    for _, bt, lo, hi in batch.shards:
+        rows.append(np.full(hi - lo, bt, np.int32))
+        pos.append(np.arange(lo, hi, dtype=np.int32))
+    rows, pos = np.concatenate(rows)[:65536], np.concatenate(pos)[:65536]
+    for name, r_, p_ in (("decode_step", last_rows, last_pos), ("bulk", rows, pos)):
+        n = len(r_)
+        kshape = (n, d.head_dim_qk) if mla else (n, d.num_kv_heads, d.head_dim_qk)
+        k_new = torch.empty(kshape, dtype=db.k_pool.dtype, device="cuda")
+        k_new.view(torch.uint8).random_(0, 120)
+        v_new = None
+        if not mla:
+            v_new = torch.empty((n, d.num_kv_heads, d.head_dim_v), dtype=db.v_pool.dtype, device="cuda")
+            v_new.view(torch.uint8).random_(0, 120)
+        rt, pt = torch.from_numpy(r_).cuda(), torch.from_numpy(p_).cuda()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(30)]
+        for a, b in evs:
+            a.record()
+            nanocp.nanocp_kv_append(db.desc, k_new, v_new, rt, pt, db.k_pool, db.v_pool, db.block_table)
+            b.record()
+        torch.cuda.synchronize()
+        us = np.array([a.elapsed_time(b) for a, b in evs])[5:] * 1e3
+        nbytes = n * (d.head_dim_qk if mla else d.num_kv_heads * (d.head_dim_qk + d.head_dim_v)) * es
+        res[name] = {"tokens": int(n), "bytes": int(nbytes), "us_mean": float(us.mean()), "us_min": float(us.min()),
+                     "GBs_written": nbytes / (us.mean() * 1e-6) / 1e9}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -174,6 +214,9 @@ def main():
                     help="skip the per_config table (step time and event-timed launch of the other workloads)")
     ap.add_argument("--no-straggle", action="store_true")
     ap.add_argument("--dump-tiles", default="", help="write the tile list and per-tile device clocks to this .npz")
+    ap.add_argument("--kv-append", action="store_true",
+                    help="time nanocp_kv_append on the workload's shapes instead of the attention step: one token per "
+                         "shard entry (what a decode step appends) and a bulk rebuild of 65536 tokens")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain device copy of known size (1 GiB read + 1 GiB written per launch); "
                          "used to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -208,6 +251,9 @@ def main():
     batch = W.FULL[args.config](with_remote_kv=False, **kw)
     d = batch.desc
     db = DeviceBatch(batch, tile_tokens=args.tile_tokens, final_rows=not args.merge_all)
+    if args.kv_append:
+        print(json.dumps(time_kv_append(batch, db, WORKLOAD_NAMES[args.config].format(n=args.num_long))))
+        return
     pools = [(db.k_pool, db.v_pool, db.k_scale, db.v_scale)]
     pools.append(tuple(None if t is None else t.clone() for t in pools[0]))
     S, R = batch.num_shards, batch.num_requests
