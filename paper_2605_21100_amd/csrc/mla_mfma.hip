@@ -146,8 +146,8 @@ __device__ inline float xor_sum(float v) {
 //              waits at each barrier for the younger one.  Wavefronts 0..3 (the older ones) issue all copies, one
 //              between every two units of their score product: their blocked time comes out of that slack and leaves
 //              the SIMD to the younger wavefront.
-// kKD: how many score-product units (two K fragments each) the LDS reads run ahead of the matrix instructions.
-template <int W, int kKD, int kOut>
+// kRing: K fragments in registers; the LDS reads run kRing - 1 matrix instructions ahead.
+template <int W, int kRing, int kOut>
 __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
   constexpr int kHq = 16 * W;        // query heads = head blocks of 16 x W
   constexpr int kDW = 32 / W;        // 16-dim blocks of V one wavefront owns (4 or 8)
@@ -287,6 +287,11 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         for (int hb = 0; hb < W; ++hb) acc[dl][hb] = f32x4{0.f, 0.f, 0.f, 0.f};
       float m_run = -INFINITY;  // integer-valued reference exponent (log2 domain) of head 16w + r, see kHeadroom
       float l_run = 0.f;        // this lane's share of the running sum of probabilities (times 2^kPShift)
+      // derived from m_run whenever it moves: which form of the exponential applies (wavefront-uniform), the integer
+      // kPShift - m_run and the factor 2^(kPShift - m_run)
+      bool p_plain = true;
+      int p_off = 0;
+      float p_unit = 0.f;
 
       // Q must count as arrived BEFORE the page loop: the compiler tracks its own global loads with the same counter
       // the page copies use, and would otherwise wait inside the loop -- at each Q fragment's first use -- for "all
@@ -335,125 +340,141 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
           wg_barrier();
         }
 
-        // ---- scores S^T[16 tokens x 16 heads] for the 4 token blocks of the page: independent accumulators, so
-        // consecutive matrix instructions do not wait for each other
-        f32x4 S[4];
-#pragma unroll
-        for (int tbk = 0; tbk < 4; ++tbk) S[tbk] = f32x4{0.f, 0.f, 0.f, 0.f};
-        // software pipeline over units u = (k-step s, token-block pair) of 2 fragments and 2 MFMAs: the fragments
-        // of unit u+kKD are read while the MFMAs of unit u run; scheduling barriers keep the compiler from hoisting
-        // all LDS reads to the top (register blow-up)
-        // the six XOR-ed lane bases of the page (everything else about a fragment's address is an immediate offset)
-        uint32_t kb[6];
+        // ---- scores and probabilities, one 16-token block at a time: S^T[16 tokens x 16 heads] = K . Q (18 matrix
+        // instructions on one accumulator), then at once the softmax of those 4 scores per lane, while the LDS reads of
+        // the next block are in flight.  The wavefront's instruction stream alternates between bursts of matrix and of
+        // vector instructions; the two wavefronts of a SIMD fall into opposite phases by themselves (whoever loses
+        // the matrix pipe is the one with vector work to do), and bursts from different wavefronts DO run
+        // concurrently (measured: 2 x {18 matrix, 30 vector} per SIMD take the time of the 36 matrix instructions
+        // alone), whereas a separate softmax phase for the whole page leaves the matrix pipes idle for its duration.
+        // This order is possible because the reference m_ref of a head is allowed to lag its running maximum (see
+        // kHeadroom): the scores of a block are turned into probabilities against the CURRENT reference, and only
+        // when one of them exceeds it by more than the headroom does the slow path below run, which also rescales
+        // what this page has produced so far.
+        uint32_t kb[6];  // the six XOR-ed lane bases of the page (the rest of a fragment's address is an immediate)
 #pragma unroll
         for (int x = 0; x < 4; ++x) kb[x] = KA ^ (uint32_t)(x << 6);
         kb[4] = KBA;
         kb[5] = KBA ^ 64u;
-        auto load_k = [&](bf16x8* kf, int u) {
-          const int s = u >> 1;
-#pragma unroll
-          for (int t2 = 0; t2 < 2; ++t2) {
-            const int tbk = 2 * (u & 1) + t2;
-            const lds_ptr kp = s < kStepsA ? lds + kb[s & 3] + (16 * tbk * kRowA + (s >> 2) * 256)
-                                           : lds + kb[4 + (s - kStepsA)] + 16 * tbk * kRowB;
-            kf[t2] = __builtin_bit_cast(bf16x8, *LDS_AS(const u32x4, kp));
-          }
+        auto load_kf = [&](int i) {  // fragment i = 18 * token block + k-step
+          const int tbk = i / kSteps, ks = i % kSteps;
+          const lds_ptr kp = ks < kStepsA ? lds + kb[ks & 3] + (16 * tbk * kRowA + (ks >> 2) * 256)
+                                          : lds + kb[4 + (ks - kStepsA)] + 16 * tbk * kRowB;
+          return __builtin_bit_cast(bf16x8, *LDS_AS(const u32x4, kp));
         };
+        u32x4 frag[2] = {u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};  // the page's probabilities as fp16 B-operand fragments:
+                                                                // token half j holds tokens 32j + 16hf + 4g + i as element 4hf + i
+        float alpha_page = 1.f;  // rescale factor of everything accumulated before this page (a power of two)
+
+        auto softmax_block = [&](int tbk, f32x4 Sb) {
+          if (ragged) {
+            // Masked token slots score -2^30 (not -inf: the general form below converts the integer part of a score
+            // to an int): exp2 of it is exactly 0.  (Scores are assumed to lie within +-2^30 in the log2 domain.)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const int tok = tok0 + 16 * tbk + 4 * g + i;
+              Sb[i] = (tok >= tb && tok < te) ? Sb[i] : kMaskedScore;
+            }
+            asm volatile("" ::: "memory");  // keeps this a branch taken on ragged pages only, not selects on every page
+          }
+          const float mx = fmaxf(fmaxf(Sb[0], Sb[1]), fmaxf(Sb[2], Sb[3]));  // raw scores: the softmax scale is positive
+          if (__any(mx * c_log2 > m_run + (float)kHeadroom)) {
+            // Slow path (a tile's first block; afterwards only when a score beats everything seen so far by a factor
+            // of 2^8): the reference of such a head moves to the ceiling of the block's maximum.
+            const float mb = xor_max(mx);            // over the 4 lane groups: all 16 tokens of the block, head r
+            const bool real = mb > -5.0e8f;           // the block holds a token of this tile's range
+            const float m_blk = __builtin_ceilf(mb * c_log2);
+            const float m_new = (real && m_blk > m_run + (float)kHeadroom) ? m_blk : m_run;
+            // 2^(m_run - m_new), exact; 0 while nothing has been accumulated (m_run = -inf)
+            const int down = (int)fmaxf(m_run - m_new, -200.f);  // <= 0
+            const float alpha = __builtin_amdgcn_ldexpf(1.f, down);
+            m_run = m_new;
+            l_run *= alpha;
+            alpha_page *= alpha;
+            // What this page has produced so far was scaled by the old reference: multiply the fp16 pairs by 2^down,
+            // as up to three packed fp16 factors of at least 2^-14 each (a single fp16 factor would underflow
+            // where the product does not; beyond 2^-42 every product is 0 anyway).
+            if (__any(down != 0)) {
+              int e = down;
+#pragma unroll
+              for (int round = 0; round < 3; ++round) {
+                const int step = e > -14 ? e : -14;
+                e -= step;
+                const uint32_t bits = (uint32_t)(step + 15) << 10;  // fp16 2^step
+                const f16x2 f = __builtin_bit_cast(f16x2, bits | (bits << 16));
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                  for (int q = 0; q < 4; ++q) {
+                    const uint32_t w = frag[j][q];  // (a bit cast applied to the vector element itself reads element 0)
+                    frag[j][q] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(f16x2, w) * f);
+                  }
+              }
+            }
+            // p * 2^kPShift = 2^frac(y) * 2^(floor(y) - m + kPShift): the significand depends on the score alone.
+            // While every reference of this wavefront lies in [-100, 118] (any sane input) that is exp2(y) * 2^(kPShift
+            // - m) with the hardware's exp2 over its normal range: three instructions per score instead of six;
+            // scores below -126 then give 0 instead of at most 2^-20 of the reference.  A head that has seen no token
+            // yet (m = -inf) takes that form with factor 0.
+            const bool none = !(m_run > -INFINITY);
+            p_plain = __all(none || (m_run >= -100.f && m_run <= 118.f));
+            p_off = none ? 0 : kPShift - (int)m_run;
+            p_unit = none ? 0.f : __builtin_amdgcn_ldexpf(1.f, p_off);
+          }
+          float pw[4];
+          if (p_plain) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pw[i] = __builtin_amdgcn_exp2f(Sb[i] * c_log2) * p_unit;
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float yv = Sb[i] * c_log2;
+              const float ex = __builtin_amdgcn_exp2f(__builtin_amdgcn_fractf(yv));
+              int fl;
+              asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(fl) : "v"(yv));  // floor(y) as an integer, one instruction
+              pw[i] = (m_run > -INFINITY) ? __builtin_amdgcn_ldexpf(ex, fl + p_off) : 0.f;
+            }
+          }
+          frag[tbk >> 1][2 * (tbk & 1)] = pack_f16(pw[0], pw[1]);
+          frag[tbk >> 1][2 * (tbk & 1) + 1] = pack_f16(pw[2], pw[3]);
+          l_run += (pw[0] + pw[1]) + (pw[2] + pw[3]);  // sum of p * 2^kPShift before the fp16 rounding
+        };
+
         auto score_product = [&](auto with_copies) {
           [[maybe_unused]] uint64_t next_src = 0;
           if constexpr (with_copies.value) next_src = page_src(pg + 1);
-          bf16x8 kf[kKD + 1][2];
+          constexpr int kFrags = 4 * kSteps;  // 72 K fragments per wavefront and page
+          bf16x8 ring[kRing];
 #pragma unroll
-          for (int u = 0; u < kKD; ++u) load_k(kf[u], u);
+          for (int i = 0; i < kRing - 1; ++i) ring[i] = load_kf(i);
 #pragma unroll
-          for (int u = 0; u < 2 * kSteps; ++u) {
-            if (u + kKD < 2 * kSteps) load_k(kf[(u + kKD) % (kKD + 1)], u + kKD);
-            if constexpr (with_copies.value) {  // one row of the next page between every two units
-              if (u % 2 == 0 && u / 2 < kPS / kND) issue_a_row(next_src, buf ^ 1, u / 2);
+          for (int tbk = 0; tbk < 4; ++tbk) {
+            f32x4 Sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < kSteps; ++ks) {
+              const int i = tbk * kSteps + ks;
+              if (i + kRing - 1 < kFrags) ring[(i + kRing - 1) % kRing] = load_kf(i + kRing - 1);
+              if constexpr (with_copies.value) {  // one row of the next page every fourth matrix instruction
+                if (i % 4 == 0 && i / 4 < kPS / kND) issue_a_row(next_src, buf ^ 1, i / 4);
+              }
+              __builtin_amdgcn_sched_barrier(0);
+              Sb = mfma_bf16(ring[i % kRing], qf[ks], Sb);
+              __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2)
-              S[2 * (u & 1) + t2] = mfma_bf16(kf[u % (kKD + 1)][t2], qf[u >> 1], S[2 * (u & 1) + t2]);
+            softmax_block(tbk, Sb);
             __builtin_amdgcn_sched_barrier(0);
           }
         };
         if (W == 8 && copies && more) score_product(std::true_type{});
         else score_product(std::false_type{});
-        // ---- online softmax of heads 16w + r (log2 domain, integer running maximum); S[tbk][i] is token
-        // tok0 + 16tbk + 4g + i.  The probabilities leave as fp16 B-operand fragments: token half j = 0, 1 holds
-        // tokens 32j + 16hf + 4g + i as element 4hf + i.
+
+        // the page's probabilities and rescale factors go to LDS
         {
-          // Masked token slots get -2^30 (not -inf): the integer part of a score goes through a float -> int
-          // conversion below, and p = 2^(-2^30 - m) underflows to exactly 0.  (Scores are assumed to lie within
-          // +-2^30 in the log2 domain.)
-          if (ragged) {
 #pragma unroll
-            for (int tbk = 0; tbk < 4; ++tbk)
-#pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                const int tok = tok0 + 16 * tbk + 4 * g + i;
-                S[tbk][i] = (tok >= tb && tok < te) ? S[tbk][i] : kMaskedScore;
-              }
-            asm volatile("" ::: "memory");  // keeps this a branch taken on ragged pages only, not 80 selects on every page
-          }
-          // maximum over the raw scores (the softmax scale is positive), scaled once
-          float mraw = fmaxf(fmaxf(S[0][0], S[0][1]), S[0][2]);
-          mraw = fmaxf(fmaxf(mraw, S[0][3]), S[1][0]);
-          mraw = fmaxf(fmaxf(mraw, S[1][1]), S[1][2]);
-          mraw = fmaxf(fmaxf(mraw, S[1][3]), S[2][0]);
-          mraw = fmaxf(fmaxf(mraw, S[2][1]), S[2][2]);
-          mraw = fmaxf(fmaxf(mraw, S[2][3]), S[3][0]);
-          mraw = fmaxf(fmaxf(mraw, S[3][1]), S[3][2]);
-          mraw = xor_max(fmaxf(mraw, S[3][3]));  // a real score: every page of the tile holds a token of its range
-          // the reference moves to the page's ceiling only if that lies more than kHeadroom above it
-          const float m_page = __builtin_ceilf(mraw * c_log2);
-          const float m_new = m_page > m_run + (float)kHeadroom ? m_page : m_run;
-          // rescale factor of everything accumulated so far: 2^(m_run - m_new), exact (0 on the first page)
-          const float alpha = __builtin_amdgcn_ldexpf(1.f, (int)fmaxf(m_run - m_new, -200.f));
-          m_run = m_new;
-          l_run *= alpha;
+          for (int j = 0; j < 2; ++j) *LDS_AS(u32x4, lds + PA + (wave * 2 + j) * 1024) = frag[j];
           const int la = fresh();  // (an address built from the kernel's lane constants would be kept across the tile loop)
-          if (la < 16) *LDS_AS(float, lds + kOffAlpha + (la * 8 + wave) * 4) = alpha;
-          if (__any(alpha != 1.f) && la == 0) *LDS_AS(int, lds + kOffMoved + buf * 4) = 1;
-          // p * 2^kPShift = 2^frac(y) * 2^(floor(y) - m + kPShift): the significand depends on the score alone.
-          // While every reference of this wavefront lies in [-100, 118] (any sane input) that is exp2(y) * 2^(kPShift -
-          // m) with the hardware's exp2 over its normal range -- three instructions per score instead of six; scores
-          // below -126 then give 0 instead of at most 2^-20 of the reference.  Outside it the general form runs.
-          int m_off = kPShift - (int)m_new;
-          asm volatile("" : "+v"(m_off));  // one integer, not re-associated into the sixteen sums below
-          const bool plain = __all(m_new >= -100.f && m_new <= 118.f);
-          // four elements at a time (scheduling barriers in between): the sixteen chains are independent, and left
-          // alone the scheduler interleaves them all, which costs more live registers than this kernel has
-          auto emit = [&](auto&& prob, auto fence_every_four) {
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-              u32x4 frag;
-#pragma unroll
-              for (int q4 = 0; q4 < 2; ++q4) {
-                float pw[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) pw[i] = prob(S[2 * j + q4][i] * c_log2);
-                frag[2 * q4] = pack_f16(pw[0], pw[1]);
-                frag[2 * q4 + 1] = pack_f16(pw[2], pw[3]);
-                l_run += (pw[0] + pw[1]) + (pw[2] + pw[3]);  // sum of p * 2^kPShift before the fp16 rounding
-                if constexpr (fence_every_four.value) __builtin_amdgcn_sched_barrier(0);
-              }
-              *LDS_AS(u32x4, lds + PA + (wave * 2 + j) * 1024) = frag;
-              __builtin_amdgcn_sched_barrier(0);
-            }
-          };
-          if (plain) {
-            const float unit = __builtin_amdgcn_ldexpf(1.f, m_off);
-            emit([&](float yv) { return __builtin_amdgcn_exp2f(yv) * unit; }, std::false_type{});
-          } else {
-            emit([&](float yv) {
-              const float ex = __builtin_amdgcn_exp2f(__builtin_amdgcn_fractf(yv));
-              int fl;
-              asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(fl) : "v"(yv));  // floor(y) as an integer, one instruction
-              return __builtin_amdgcn_ldexpf(ex, fl + m_off);
-            }, std::true_type{});
-          }
+          if (la < 16) *LDS_AS(float, lds + kOffAlpha + (la * 8 + wave) * 4) = alpha_page;
+          if (__any(alpha_page != 1.f) && la == 0) *LDS_AS(int, lds + kOffMoved + buf * 4) = 1;
         }
         uint32_t VA;
         {
@@ -732,12 +753,12 @@ __global__ __launch_bounds__(256) void mla_reduce_kernel(KParams p, const Seg* _
 // Both kernels: 8 wavefronts, two per SIMD, 256 registers each.  128 heads: all of them compute.
 template <int kOut>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void mla_mfma_kernel(KParams p) {
-  mla_mfma_body<8, 1, kOut>(p);
+  mla_mfma_body<8, 4, kOut>(p);
 }
 // 64 heads: four compute, four copy
 template <int kOut>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void mla64_mfma_kernel(KParams p) {
-  mla_mfma_body<4, 1, kOut>(p);
+  mla_mfma_body<4, 4, kOut>(p);
 }
 
 // The dynamic-LDS limit is an attribute of the kernel on ONE device: it is raised once per device and kernel, with
