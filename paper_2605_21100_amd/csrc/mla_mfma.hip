@@ -249,19 +249,52 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
       };
 
       if (!computes) {
-        // a copying-only wavefront (64-head kernel): the same barriers as the computing ones, and the copies of the
-        // next page in between
-        issue_page_a(pg0, 0);
-        issue_page_rope(pg0);
+        // A copying-only wavefront (64-head kernel): the same barriers as the computing ones.  It has registers to
+        // spare, so its share of a page (16 rows of the V part, 2 rope slabs: 18 KB) travels through registers --
+        // ordinary 16-byte global loads, then ds_write_b128 -- instead of direct-to-LDS copies: that path tops out
+        // near 6 TB/s over the whole chip (measured with nothing else running), below what this kernel can consume,
+        // and a page staged in registers can be requested a whole page earlier than its LDS buffer becomes free.
+        const int l = fresh();
+        u32x4 va[kPS / kND], vr[8 / kND];
+        auto fetch = [&](int pg) {  // same placement as the direct copies: position l of row tok holds chunk l ^ (tok & 15)
+          const char* src = (const char*)(uintptr_t)page_src(pg);
+#pragma unroll
+          for (int j = 0; j < kPS / kND; ++j) {
+            const int tok = cw + kND * j;
+            va[j] = __builtin_nontemporal_load((const u32x4*)(src + (uint32_t)(tok * kRowBytes + ((l ^ (tok & 15)) << 4))));
+          }
+#pragma unroll
+          for (int a = 0; a < 8 / kND; ++a) {
+            const int slab = (8 / kND) * cw + a;
+            const int row = 8 * slab + (l >> 3);
+            vr[a] = __builtin_nontemporal_load(
+                (const u32x4*)(src + (uint32_t)(row * kRowBytes + kRowA + (((l & 7) ^ ((row >> 1) & 7)) << 4))));
+          }
+        };
+        auto store_a = [&](int buf) {
+#pragma unroll
+          for (int j = 0; j < kPS / kND; ++j)
+            *LDS_AS(u32x4, lds + buf * kRegionA + (cw + kND * j) * kRowA + l * 16) = va[j];
+        };
+        auto store_rope = [&]() {
+#pragma unroll
+          for (int a = 0; a < 8 / kND; ++a) *LDS_AS(u32x4, lds + kOffRope + ((8 / kND) * cw + a) * 1024 + l * 16) = vr[a];
+        };
+        fetch(pg0);
+        store_a(0);
+        store_rope();
+        if (pg0 + 1 < pg1) fetch(pg0 + 1);  // in flight while the computing wavefronts work on the first page
         for (int pg = pg0; pg < pg1; ++pg) {
           const int tok0 = pg * kPS;
-          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wavefront's share of page pg is in LDS
           wg_barrier();                                        // top of the page
           if (tok0 < tb || tok0 + kPS > te) wg_barrier();      // ragged page: after the clearing of unused rows
-          if (pg + 1 < pg1) issue_page_a(pg + 1, ((pg - pg0) & 1) ^ 1);
+          if (pg + 1 < pg1) store_a(((pg - pg0) & 1) ^ 1);     // that buffer was last read by P.V of page pg - 1
           wg_barrier();                                        // probabilities written; the rope buffer is free
-          if (pg + 1 < pg1) issue_page_rope(pg + 1);
+          if (pg + 1 < pg1) store_rope();
+          if (pg + 2 < pg1) fetch(pg + 2);
         }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         wg_barrier();  // the two barriers of the tile epilogue
         wg_barrier();
         continue;
