@@ -256,19 +256,26 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         // and a page staged in registers can be requested a whole page earlier than its LDS buffer becomes free.
         const int l = fresh();
         u32x4 va[kPS / kND], vr[8 / kND];
-        auto fetch = [&](int pg) {  // same placement as the direct copies: position l of row tok holds chunk l ^ (tok & 15)
-          const char* src = (const char*)(uintptr_t)page_src(pg);
+        // (global address space stated explicitly: through a generic pointer these would be FLAT loads, which count on
+        // the LDS counter as well)  Same placement as the direct copies: position l of row tok holds chunk l ^ (tok & 15).
+        typedef const __attribute__((address_space(1))) char* gchar;
+        typedef const __attribute__((address_space(1))) u32x4* gvec;
+        auto fetch_rows = [&](int pg) {
+          const gchar src = (gchar)(uintptr_t)page_src(pg);
 #pragma unroll
           for (int j = 0; j < kPS / kND; ++j) {
             const int tok = cw + kND * j;
-            va[j] = __builtin_nontemporal_load((const u32x4*)(src + (uint32_t)(tok * kRowBytes + ((l ^ (tok & 15)) << 4))));
+            va[j] = __builtin_nontemporal_load((gvec)(src + (uint32_t)(tok * kRowBytes + ((l ^ (tok & 15)) << 4))));
           }
+        };
+        auto fetch_rope = [&](int pg) {
+          const gchar src = (gchar)(uintptr_t)page_src(pg);
 #pragma unroll
           for (int a = 0; a < 8 / kND; ++a) {
             const int slab = (8 / kND) * cw + a;
             const int row = 8 * slab + (l >> 3);
             vr[a] = __builtin_nontemporal_load(
-                (const u32x4*)(src + (uint32_t)(row * kRowBytes + kRowA + (((l & 7) ^ ((row >> 1) & 7)) << 4))));
+                (gvec)(src + (uint32_t)(row * kRowBytes + kRowA + (((l & 7) ^ ((row >> 1) & 7)) << 4))));
           }
         };
         auto store_a = [&](int buf) {
@@ -280,19 +287,28 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
 #pragma unroll
           for (int a = 0; a < 8 / kND; ++a) *LDS_AS(u32x4, lds + kOffRope + ((8 / kND) * cw + a) * 1024 + l * 16) = vr[a];
         };
-        fetch(pg0);
+        fetch_rows(pg0);
+        fetch_rope(pg0);
         store_a(0);
         store_rope();
-        if (pg0 + 1 < pg1) fetch(pg0 + 1);  // in flight while the computing wavefronts work on the first page
+        if (pg0 + 1 < pg1) {  // in flight while the computing wavefronts work on the first page
+          fetch_rows(pg0 + 1);
+          fetch_rope(pg0 + 1);
+        }
         for (int pg = pg0; pg < pg1; ++pg) {
           const int tok0 = pg * kPS;
           asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wavefront's share of page pg is in LDS
           wg_barrier();                                        // top of the page
           if (tok0 < tb || tok0 + kPS > te) wg_barrier();      // ragged page: after the clearing of unused rows
-          if (pg + 1 < pg1) store_a(((pg - pg0) & 1) ^ 1);     // that buffer was last read by P.V of page pg - 1
+          // The rows of page pg + 1 go to LDS (that buffer was last read by the P.V of page pg - 1) and the rows of
+          // page pg + 2 are requested at once: they have a whole page time to arrive.
+          if (pg + 1 < pg1) store_a(((pg - pg0) & 1) ^ 1);
+          if (pg + 2 < pg1) fetch_rows(pg + 2);
+          asm volatile("" ::: "memory");  // (keeps the loads here: the compiler otherwise sinks them towards their use)
           wg_barrier();                                        // probabilities written; the rope buffer is free
           if (pg + 1 < pg1) store_rope();
-          if (pg + 2 < pg1) fetch(pg + 2);
+          if (pg + 2 < pg1) fetch_rope(pg + 2);
+          asm volatile("" ::: "memory");
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         wg_barrier();  // the two barriers of the tile epilogue
