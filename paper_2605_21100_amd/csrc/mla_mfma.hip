@@ -213,8 +213,7 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         tile.tok_begin = w[4], tile.tok_end = w[5], tile.dst = w[6], tile.seg = w[7];
         tile.n_parts = w[8], tile.slot_begin = w[9], tile.final_row = w[10], tile.lse_shard = w[11];
       }
-      uint64_t clk0 = 0;
-      if (p.tile_clock) clk0 = wall_clock64();
+      const uint64_t clk0 = wall_clock64();  // (unconditional: a scalar read; the condition would cost a register)
       const cptr<int32_t> bt = as_const(p.block_table + (size_t)tile.bt_row * p.max_blocks);
       const int tb = tile.tok_begin, te = tile.tok_end;
       const int pg0 = tb / kPS, pg1 = (te - 1) / kPS + 1;  // pages [pg0, pg1) of the row
