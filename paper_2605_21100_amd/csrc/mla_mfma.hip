@@ -1,30 +1,31 @@
-// MFMA tile kernel for MLA-absorbed decode (DeepSeek-V3-like shapes): 128 query heads (or 64, with 4 wavefronts)
-// share one latent row of 576 dims per token (512 latent + 64 rope); V is the first 512 dims of the same row, so a
-// page is read from HBM once and used for both products.  bf16, page size 64.
+// MFMA tile kernels for MLA-absorbed decode (DeepSeek-V3-like shapes): 128 query heads (or 64) share one latent
+// row of 576 dims per token (512 latent + 64 rope); V is the first 512 dims of the same row, so a page is read from
+// HBM once and used for both products.  bf16, page size 64.
 // Paper: Data Plane, Phase 2 (partial attention + LSE over the local KV partition); the MoE-bound
 // instance's Q row has hidden size 512 (+64) and 128 heads.
 //
-// One workgroup = W wavefronts (8 for 128 heads: two per SIMD) = one chunk of the work queue at a time, one
-// workgroup per CU.  A page (72 KB) is copied HBM -> LDS by direct-to-LDS 16-byte loads (no registers in between)
-// while the previous page is being computed.  The two products are split over the wavefronts in different ways:
+// One workgroup = 8 wavefronts (two per SIMD) = one chunk of the work queue at a time, one workgroup per CU.  A page
+// (72 KB) sits in LDS while it is computed on, the next one arrives meanwhile (who copies it: see mla_mfma_body).  The
+// two products are split over the computing wavefronts (all 8 with 128 heads, 4 with 64) in different ways:
 //   scores (split by heads):  wavefront w owns query heads 16w..16w+15, its Q fragments stay in registers
 //       S^T[token, head] = K[token, :] . Q[head, :]          A = K rows from LDS (ds_read_b128), B = Q
-//     followed by the online softmax of those heads; the probabilities go to LDS as fp16 B-operand fragments.
-//   output (split by V dims): wavefront w owns dims 512/W * w .. of ALL heads (accumulator 512/W x 16W, 128 registers)
+//     one 16-token block at a time, each followed at once by the softmax of its scores; the page's probabilities go
+//     to LDS as fp16 B-operand fragments.
+//   output (split by V dims): wavefront w owns a slice of the 512 dims of ALL heads (accumulator 128 registers)
 //       O^T[dim, head] += V^T[dim, token] P^T[token, head]   A = V^T via the LDS transpose read
 //       (ds_read_b64_tr_b16: 16 lanes fetch a 4-token x 16-dim block, each lane gets 4 tokens of one dim), B = P
-//     so every V^T fragment is fetched from LDS once per page (not once per wavefront) and feeds 16W / 16 matrix
-//     instructions; the only data all wavefronts read are the probabilities (16 KB per page, 16-byte reads).
+//     so every V^T fragment is fetched from LDS once per page (not once per wavefront) and feeds one matrix
+//     instruction per head block; the only data all wavefronts read are the probabilities (16 KB per page).
 // Precision of P.  One fp16 term (11 significant bits) instead of the two bf16 terms of the GQA kernels: the P.V
 // product is then half the matrix instructions.  Two things make that sufficient:
-//   * the softmax reference is an INTEGER exponent m (a ceiling of log2-domain scores, see kHeadroom), and
-//     p = 2^frac(y) * 2^(floor(y) - m): the significand of p does not depend on m, every rescale is an exact
-//     power of two, so a token's rounded probability is the same number (up to that power of two) whatever tile
-//     or shard it is processed in -- a request's merged partials and its unsharded result differ only by fp32
-//     summation order;
+//   * the softmax reference is an INTEGER exponent m (a ceiling of log2-domain scores that may lag the running
+//     maximum, see kHeadroom), and p = 2^frac(y) * 2^(floor(y) - m): the significand of p does not depend on m,
+//     every rescale is an exact power of two, so a token's rounded probability is the same number (up to that power
+//     of two) whatever tile or shard it is processed in -- a request's merged partials and its unsharded result
+//     differ only by fp32 summation order;
 //   * V (bf16, 8 significant bits) is widened to fp16 exactly (in registers, by the wavefront that owns the dims).
 //     fp16's range applies: |V| above 65504 saturates, |V| below 6e-8 flushes to zero.  P is scaled by a power of
-//     two so that probabilities down to 2^-28 of the largest possible maximum stay normal fp16 numbers.
+//     two so that probabilities down to 2^-20 of the reference stay normal fp16 numbers.
 // LDS rows are XOR-swizzled in units of 16 bytes so that both read patterns are bank-conflict free.
 // The tiles of one (shard, head-set) that was cut are combined by mla_reduce_kernel below, launched right after the
 // tile kernel (it also writes the rows of shards without tokens).
