@@ -757,17 +757,18 @@ __global__ __launch_bounds__(256) void mla_reduce_kernel(KParams p, const Seg* _
     float li[8];
     f32x4 v[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const size_t slot = (size_t)(sg.slot_begin + min(k0 + j, sg.n_parts - 1));
-      li[j] = p.ws_lse[slot * kHq + head];
-      v[j] = *(const f32x4*)(p.ws_o + slot * per_tile + (size_t)u * 4);
+    for (int j = 0; j < 8; ++j) {  // (the part count is the same for the whole workgroup: no load is issued twice)
+      li[j] = -INFINITY;
+      v[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (k0 + j < sg.n_parts) {
+        const size_t slot = (size_t)(sg.slot_begin + k0 + j);
+        li[j] = p.ws_lse[slot * kHq + head];
+        v[j] = *(const f32x4*)(p.ws_o + slot * per_tile + (size_t)u * 4);
+      }
     }
     float bm = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      if (k0 + j >= sg.n_parts) li[j] = -INFINITY;
-      bm = fmaxf(bm, li[j]);
-    }
+    for (int j = 0; j < 8; ++j) bm = fmaxf(bm, li[j]);
     const float nt = fmaxf(top, bm);  // finite: tile partials are never empty
     const float sc = expf(top - nt);
     tot *= sc;
