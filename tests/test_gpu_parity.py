@@ -485,7 +485,7 @@ def test_final_rows_errors():
     db.plan.close()
 
 
-@pytest.mark.parametrize("cid", [1, 2, 4, 5])
+@pytest.mark.parametrize("cid", [1, 2, 4, 5, 7])
 def test_peaked_scores_exercise_the_running_maximum(cid):
     """Queries scaled by 32 (exact in every input type): scores spread over hundreds of log2 units, the softmax is
     nearly one-hot and the running maximum moves again and again inside a tile - the rescaling paths, the masked
