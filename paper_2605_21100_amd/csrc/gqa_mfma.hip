@@ -470,16 +470,38 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
         if (arrive_is_last(&p.sync[kSyncSegBase + tile.seg], tile.n_parts, &arrive_s)) {
           const float* wl = p.ws_lse + (size_t)tile.slot_begin * kG + n;
           const float* wo = p.ws_o + ((size_t)tile.slot_begin * kG + n) * kD + c16;
-          float top = -INFINITY;
-          for (int k = 0; k < tile.n_parts; ++k) top = fmaxf(top, ld_dev(wl + (size_t)k * kG));
-          float tot = 0.f, r8[8];
+          // One pass with a running maximum, four partials at a time: their 36 loads are issued together, so a
+          // segment of n partials costs ceil(n / 4) memory round trips on this workgroup (it is the last one of the
+          // segment: nothing else hides them).  Tile partials are never empty: every LSE is finite.
+          float top = -INFINITY, tot = 0.f, r8[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) r8[e] = 0.f;
-          for (int k = 0; k < tile.n_parts; ++k) {
-            const float w = expf(ld_dev(wl + (size_t)k * kG) - top);
-            tot += w;
+          for (int k0 = 0; k0 < tile.n_parts; k0 += 4) {
+            float lw[4], v[4][8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) r8[e] = fmaf(w, ld_dev(wo + (size_t)k * kG * kD + 16 * e), r8[e]);
+            for (int j = 0; j < 4; ++j) {
+              lw[j] = -INFINITY;
+#pragma unroll
+              for (int e = 0; e < 8; ++e) v[j][e] = 0.f;
+              if (k0 + j < tile.n_parts) {  // uniform over the workgroup
+                lw[j] = ld_dev(wl + (size_t)(k0 + j) * kG);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[j][e] = ld_dev(wo + (size_t)(k0 + j) * kG * kD + 16 * e);
+              }
+            }
+            const float nt = fmaxf(fmaxf(top, fmaxf(lw[0], lw[1])), fmaxf(lw[2], lw[3]));
+            const float sc = expf(top - nt);  // 0 on the first batch (top = -inf)
+            tot *= sc;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) r8[e] *= sc;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const float w = expf(lw[j] - nt);  // 0 for the padding of the last batch
+              tot += w;
+#pragma unroll
+              for (int e = 0; e < 8; ++e) r8[e] = fmaf(w, v[j][e], r8[e]);
+            }
+            top = nt;
           }
           const float rinv = 1.f / tot;
           const float lse_f = top + logf(tot);
