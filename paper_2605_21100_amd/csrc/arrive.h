@@ -4,7 +4,7 @@
 // with each other for ordinary accesses).
 //
 // What makes a partial visible to the reducer, step by step:
-//   producer  (1) every partial word is written with a device-scope store (st_dev: relaxed atomic store, agent scope
+//   producer  (1) every partial word is written with a device-scope store (st_dev, st_dev2: relaxed atomic store, agent scope
 //                 -> a store that is performed at the device's point of coherence, not left dirty in this XCD's L2);
 //             (2) every thread waits until all its stores have been acknowledged (s_waitcnt vmcnt(0)); for a
 //                 device-scope store the acknowledgement means it has been performed at that point of coherence.
@@ -18,7 +18,7 @@
 //             (6) its result reaches the workgroup through LDS and a barrier, and the branch on it is a control
 //                 dependency: no partial load is issued before the count is known (the hardware issues a
 //                 wavefront's memory instructions in order and does not speculate past the branch);
-//             (7) the partials are read with device-scope loads (ld_dev), each served from the point of coherence,
+//             (7) the partials are read with device-scope loads (ld_dev, ld_dev2), each served from the point of coherence,
 //                 never from a stale line of this XCD's L2 or the CU's L1.
 // What the compiler may move: the relaxed atomics are not reordered with each other across the inline-asm wait,
 // the fence and the barrier (all three are compiler barriers for memory operations); ordinary loads/stores of
@@ -37,6 +37,17 @@ __device__ inline void st_dev(float* ptr, float v) {
 }
 __device__ inline float ld_dev(const float* ptr) {
   return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// the same for two floats at once (8-byte device-scope accesses; `ptr` 8-byte aligned)
+__device__ inline void st_dev2(float* ptr, float a, float b) {
+  const uint64_t w = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
+  __hip_atomic_store((uint64_t*)ptr, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void ld_dev2(const float* ptr, float& a, float& b) {
+  const uint64_t w = __hip_atomic_load((const uint64_t*)ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  a = __uint_as_float((uint32_t)w);
+  b = __uint_as_float((uint32_t)(w >> 32));
 }
 
 // Steps (2)-(6).  Call from every thread of the workgroup after its st_dev stores; `flag` is an int in LDS.

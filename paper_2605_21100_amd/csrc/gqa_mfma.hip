@@ -456,20 +456,23 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
       } else {
         // one of several tiles: publish the partial, and let the workgroup that delivers the last one
         // LSE-combine them (same operator as the Phase 4 merge) into the shard's rows.  Here the thread owns
-        // dims c16 + 16e, so that each of the 4-byte device-scope stores / loads of 16 neighbouring lanes
-        // covers one whole 64-byte sector.
+        // the dim pairs 2 c16 + 32 e, + 1, so that each of the 8-byte device-scope stores / loads of 16 neighbouring
+        // lanes covers 128 contiguous bytes (a device-scope access costs per instruction: four instead of eight).
 #pragma unroll
         for (int w = 0; w < kWaves; ++w)
 #pragma unroll
-          for (int e = 0; e < 8; ++e) o[e] = fmaf(f[w], o_s[w][n][c16 + 16 * e], o[e]);
-        float* dst_o = p.ws_o + ((size_t)tile.dst * kG + n) * kD + c16;
+          for (int e = 0; e < 4; ++e) {
+            o[2 * e] = fmaf(f[w], o_s[w][n][2 * c16 + 32 * e], o[2 * e]);
+            o[2 * e + 1] = fmaf(f[w], o_s[w][n][2 * c16 + 32 * e + 1], o[2 * e + 1]);
+          }
+        float* dst_o = p.ws_o + ((size_t)tile.dst * kG + n) * kD + 2 * c16;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) st_dev(dst_o + 16 * e, o[e]);
+        for (int e = 0; e < 4; ++e) st_dev2(dst_o + 32 * e, o[2 * e], o[2 * e + 1]);
         if (c16 == 0) st_dev(p.ws_lse + (size_t)tile.dst * kG + n, lse_nat);
         // publish, count the arrival, and reduce if this workgroup delivered the last partial (csrc/arrive.h)
         if (arrive_is_last(&p.sync[kSyncSegBase + tile.seg], tile.n_parts, &arrive_s)) {
           const float* wl = p.ws_lse + (size_t)tile.slot_begin * kG + n;
-          const float* wo = p.ws_o + ((size_t)tile.slot_begin * kG + n) * kD + c16;
+          const float* wo = p.ws_o + ((size_t)tile.slot_begin * kG + n) * kD + 2 * c16;
           // One pass with a running maximum, four partials at a time: their 36 loads are issued together, so a
           // segment of n partials costs ceil(n / 4) memory round trips on this workgroup (it is the last one of the
           // segment: nothing else hides them).  Tile partials are never empty: every LSE is finite.
@@ -486,7 +489,7 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
               if (k0 + j < tile.n_parts) {  // uniform over the workgroup
                 lw[j] = ld_dev(wl + (size_t)(k0 + j) * kG);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[j][e] = ld_dev(wo + (size_t)(k0 + j) * kG * kD + 16 * e);
+                for (int e = 0; e < 4; ++e) ld_dev2(wo + (size_t)(k0 + j) * kG * kD + 32 * e, v[j][2 * e], v[j][2 * e + 1]);
               }
             }
             const float nt = fmaxf(fmaxf(top, fmaxf(lw[0], lw[1])), fmaxf(lw[2], lw[3]));
@@ -508,17 +511,17 @@ __global__ __launch_bounds__(kThreads, 1) void gqa_mfma_kernel(KParams p) {
           // (shards reduced as one group deliver the row's LSE at the group's first shard, whoever arrives last)
           if (c16 == 0) p.out_lse[(size_t)tile.lse_shard * p.Hq + (size_t)h * kG + n] = lse_f;
           if (p.final_out && tile.final_row >= 0) {
-            const size_t fi = ((size_t)tile.final_row * p.Hq + (size_t)h * kG + n) * kD + c16;
+            const size_t fi = ((size_t)tile.final_row * p.Hq + (size_t)h * kG + n) * kD + 2 * c16;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
               const float v1[1] = {r8[e] * rinv};
-              store_final<1>(p.final_out, fi + 16 * e, kOut, p.out_inv_scale, v1);
+              store_final<1>(p.final_out, fi + 32 * (e >> 1) + (e & 1), kOut, p.out_inv_scale, v1);
             }
             if (c16 == 0 && p.final_lse) p.final_lse[(size_t)tile.final_row * p.Hq + (size_t)h * kG + n] = lse_f;
           } else {
-            float* fo = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG + n) * kD + c16;
+            float* fo = p.out_o + ((size_t)tile.shard * p.Hq + (size_t)h * kG + n) * kD + 2 * c16;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) fo[16 * e] = r8[e] * rinv;
+            for (int e = 0; e < 4; ++e) *(float2*)(fo + 32 * e) = make_float2(r8[2 * e] * rinv, r8[2 * e + 1] * rinv);
           }
           if (tid == 0) arrive_reset(&p.sync[kSyncSegBase + tile.seg]);  // ready for the next launch
         }
