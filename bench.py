@@ -28,7 +28,7 @@ MEASURED_TRAFFIC_BYTES = {3: (1203400000, "profiles/gqa_mfma_bf16_config3_mixed_
                           5: (764320000, "profiles/gqa_mfma_fp8_config5_long_shard.md"),
                           2: (656040000, "profiles/gqa_mfma_bf16_config2_local.md"),
                           4: (1585600000, "profiles/mla_mfma_bf16_config4.md"),
-                          6: (677250000, "profiles/gqa_mfma_bf16_config6_microbench.md"),   # 3 long requests per node
+                          6: (677260000, "profiles/gqa_mfma_bf16_config6_microbench.md"),   # 3 long requests per node
                           7: (1468200000, "profiles/mla64_mfma_bf16_config7.md")}
 METRIC = "decode-attention KV GB/s (% of HBM peak) + µs/step, mixed ragged DCP batch"
 WORKLOAD_NAMES = {1: "config1: tiny fp32 GQA", 2: "config2: bf16 GQA 64 local requests U[1024,8192]",
