@@ -604,8 +604,12 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
         };
 #pragma unroll
         for (int dh = 0; dh < kDW / kDB; ++dh) {  // one pass (128 heads) or four (64 heads)
-          f16x8 pf[2];
-          pf[0] = load_p(0, 0);
+          // probability fragments are requested kPF - 1 units ahead (64 heads: two, one wavefront per SIMD has
+          // nobody to hide an LDS latency behind; 128 heads: one, there is no register for a third fragment)
+          constexpr int kPF = W == 8 ? 2 : 3;
+          f16x8 pf[kPF];
+#pragma unroll
+          for (int a = 0; a < kPF - 1; ++a) pf[a] = load_p(a % W, a / W);
           __builtin_amdgcn_sched_barrier(0);
           f16x8 vf[kDB];
 #pragma unroll
@@ -614,7 +618,7 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
 #pragma unroll
           for (int u = 0; u < 2 * W; ++u) {  // units (j, hb): one probability fragment feeds kDB matrix instructions
             const int j = u / W, hb = u % W;
-            if (u + 1 < 2 * W) pf[(u + 1) & 1] = load_p((u + 1) % W, (u + 1) / W);
+            if (u + kPF - 1 < 2 * W) pf[(u + kPF - 1) % kPF] = load_p((u + kPF - 1) % W, (u + kPF - 1) / W);
             // the raw V^T fragments needed next (this pass's second token half, then the next pass's first) are
             // requested during the current half's units, one per unit over its last kDB units
             constexpr int kFirst = W - kDB;
@@ -622,7 +626,7 @@ __device__ __forceinline__ void mla_mfma_body(const KParams& p) {
             if (hb >= kFirst && (j == 0 || next_pass)) raw[hb - kFirst] = load_v_raw(kDB * (dh + (j == 1 ? 1 : 0)) + hb - kFirst, j ^ 1);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int dl = 0; dl < kDB; ++dl) acc[kDB * dh + dl][hb] = mfma_f16(vf[dl], pf[u & 1], acc[kDB * dh + dl][hb]);
+            for (int dl = 0; dl < kDB; ++dl) acc[kDB * dh + dl][hb] = mfma_f16(vf[dl], pf[u % kPF], acc[kDB * dh + dl][hb]);
             __builtin_amdgcn_sched_barrier(0);
             if (u == W - 1 || (u == 2 * W - 1 && dh + 1 < kDW / kDB)) {
 #pragma unroll
