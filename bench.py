@@ -29,7 +29,7 @@ MEASURED_TRAFFIC_BYTES = {3: (1203400000, "profiles/gqa_mfma_bf16_config3_mixed_
                           2: (656040000, "profiles/gqa_mfma_bf16_config2_local.md"),
                           4: (1585600000, "profiles/mla_mfma_bf16_config4.md"),
                           6: (677260000, "profiles/gqa_mfma_bf16_config6_microbench.md"),   # 3 long requests per node
-                          7: (1468200000, "profiles/mla64_mfma_bf16_config7.md")}
+                          7: (1468300000, "profiles/mla64_mfma_bf16_config7.md")}
 METRIC = "decode-attention KV GB/s (% of HBM peak) + µs/step, mixed ragged DCP batch"
 WORKLOAD_NAMES = {1: "config1: tiny fp32 GQA", 2: "config2: bf16 GQA 64 local requests U[1024,8192]",
                   3: "config3: mixed long-tail DCP batch, 128 requests lognormal(median 2048, sigma 1.2), bf16 GQA 64q/4kv d128",
